@@ -1,0 +1,179 @@
+"""CPU oracle for the PicoSpec separate-rejection-sampling path.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py``.  Nothing in the product package imports this, and this
+package imports nothing from the product package.
+
+The arithmetic lives in ``picospec_oracle.c`` (plain C, fp64); this module only builds it with gcc
+and marshals numpy arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "picospec_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+F32, BF16 = 0, 1
+FLAG_TOKEN_NOT_IN_SUPPORT, FLAG_NONFINITE, FLAG_RESIDUAL_EMPTY = 1, 2, 4
+
+
+def build() -> str:
+    """Compile the C oracle (no fast-math, so libm exp/log and IEEE ordering are kept)."""
+    cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+            build()
+        _lib = C.CDLL(_LIB)
+        for name in ("oracle_compress", "oracle_sample_draft", "oracle_verify",
+                     "oracle_sample_residual", "oracle_record_bytes"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def threads() -> int:
+    """Host threads the OpenMP loops use (what ``cores`` in the bench line reports)."""
+    n = os.environ.get("OMP_NUM_THREADS")
+    return int(n) if n else (os.cpu_count() or 1)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _logits(a: np.ndarray):
+    """Accepts float32 [rows, ld] or uint16 [rows, ld] holding bf16 bit patterns."""
+    assert a.ndim == 2 and a.flags.c_contiguous
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"logits must be float32 or uint16(bf16 bits), got {a.dtype}")
+
+
+@dataclass
+class Compressed:
+    idx: np.ndarray      # int32 [rows, k]
+    prob: np.ndarray     # float64 [rows, k]
+    count: np.ndarray    # int32 [rows]
+    mass: np.ndarray     # float64 [rows]
+    lse: np.ndarray      # float64 [rows]
+    topp_margin: np.ndarray  # float64 [rows]
+    k: int
+
+
+def compress(logits: np.ndarray, V: int, T: float, k: int, top_p: float = 0.0) -> Compressed:
+    dt = _logits(logits)
+    n, ld = logits.shape
+    out = Compressed(np.empty((n, k), np.int32), np.empty((n, k), np.float64),
+                     np.empty(n, np.int32), np.empty(n, np.float64), np.empty(n, np.float64),
+                     np.empty(n, np.float64), k)
+    rc = lib().oracle_compress(_ptr(logits), C.c_int(dt), C.c_int64(ld), C.c_int32(n), C.c_int32(V),
+                               C.c_double(T), C.c_int32(k), C.c_double(top_p),
+                               _ptr(out.idx), _ptr(out.prob), _ptr(out.count), _ptr(out.mass),
+                               _ptr(out.lse), _ptr(out.topp_margin))
+    if rc != 0:
+        raise ValueError(f"oracle_compress rc={rc}")
+    return out
+
+
+def sample_draft(q: Compressed, uniforms: np.ndarray):
+    """-> (tok int32 [rows], slot int32 [rows], cdf_margin float64 [rows])."""
+    n = q.idx.shape[0]
+    u = np.ascontiguousarray(uniforms, np.float32)
+    assert u.shape == (n,)
+    tok, slot, mar = np.empty(n, np.int32), np.empty(n, np.int32), np.empty(n, np.float64)
+    rc = lib().oracle_sample_draft(_ptr(q.idx), _ptr(q.prob), _ptr(q.count), C.c_int32(q.k),
+                                   C.c_int32(n), _ptr(u), _ptr(tok), _ptr(slot), _ptr(mar))
+    if rc != 0:
+        raise ValueError(f"oracle_sample_draft rc={rc}")
+    return tok, slot, mar
+
+
+@dataclass
+class Verified:
+    n_accept: np.ndarray   # int32 [B]
+    p_tok: np.ndarray      # float64 [N]
+    q_tok: np.ndarray      # float64 [N]
+    tgt_lse: np.ndarray    # float64 [N+B]
+    flags: np.ndarray      # uint32 [B]
+    margin: np.ndarray     # float64 [N]
+
+
+def verify(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray, draft_tok: np.ndarray,
+           q: Compressed | None, uniforms: np.ndarray, renorm: int = 1,
+           q_scalar: np.ndarray | None = None) -> Verified:
+    dt = _logits(tgt_logits)
+    rows, ld = tgt_logits.shape
+    seq_off = np.ascontiguousarray(seq_off, np.int32)
+    B = seq_off.shape[0] - 1
+    N = int(seq_off[-1])
+    assert rows >= N + B
+    draft_tok = np.ascontiguousarray(draft_tok, np.int32)
+    u = np.ascontiguousarray(uniforms, np.float32)
+    assert draft_tok.shape == (N,) and u.shape[0] >= N + B
+    qs = None if q_scalar is None else np.ascontiguousarray(q_scalar, np.float64)
+    out = Verified(np.empty(B, np.int32), np.empty(N, np.float64), np.empty(N, np.float64),
+                   np.empty(N + B, np.float64), np.zeros(B, np.uint32), np.empty(N, np.float64))
+    k = q.k if q is not None else 1
+    rc = lib().oracle_verify(_ptr(tgt_logits), C.c_int(dt), C.c_int64(ld), C.c_int32(V), C.c_double(T),
+                             C.c_int32(B), _ptr(seq_off), _ptr(draft_tok),
+                             _ptr(q.idx) if q else None, _ptr(q.prob) if q else None,
+                             _ptr(q.count) if q else None, _ptr(q.mass) if q else None,
+                             C.c_int32(k), C.c_int(renorm), _ptr(qs), _ptr(u),
+                             _ptr(out.n_accept), _ptr(out.p_tok), _ptr(out.q_tok), _ptr(out.tgt_lse),
+                             _ptr(out.flags), _ptr(out.margin))
+    if rc != 0:
+        raise ValueError(f"oracle_verify rc={rc}")
+    return out
+
+
+@dataclass
+class Residual:
+    out_tok: np.ndarray     # int32 [B]
+    resid_mass: np.ndarray  # float64 [B]
+    flags: np.ndarray       # uint32 [B]
+    cdf_margin: np.ndarray  # float64 [B]
+
+
+def sample_residual(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray,
+                    n_accept: np.ndarray, tgt_lse: np.ndarray, q: Compressed,
+                    uniforms: np.ndarray, renorm: int = 1) -> Residual:
+    dt = _logits(tgt_logits)
+    _, ld = tgt_logits.shape
+    seq_off = np.ascontiguousarray(seq_off, np.int32)
+    B = seq_off.shape[0] - 1
+    n_accept = np.ascontiguousarray(n_accept, np.int32)
+    tgt_lse = np.ascontiguousarray(tgt_lse, np.float64)
+    u = np.ascontiguousarray(uniforms, np.float32)
+    out = Residual(np.empty(B, np.int32), np.empty(B, np.float64), np.zeros(B, np.uint32),
+                   np.empty(B, np.float64))
+    rc = lib().oracle_sample_residual(_ptr(tgt_logits), C.c_int(dt), C.c_int64(ld), C.c_int32(V),
+                                      C.c_double(T), C.c_int32(B), _ptr(seq_off), _ptr(n_accept),
+                                      _ptr(tgt_lse), _ptr(q.idx), _ptr(q.prob), _ptr(q.count),
+                                      _ptr(q.mass), C.c_int32(q.k), C.c_int(renorm), _ptr(u),
+                                      _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
+                                      _ptr(out.cdf_margin))
+    if rc != 0:
+        raise ValueError(f"oracle_sample_residual rc={rc}")
+    return out
+
+
+def record_bytes() -> int:
+    return lib().oracle_record_bytes()
