@@ -1,0 +1,153 @@
+/*
+ * picospec.h -- C ABI of the MI355X (gfx950) implementation of PicoSpec's separate rejection
+ * sampling with sparse compression (paper Section 3.3).
+ *
+ * One speculative round over B sequences, sequence b having gamma_b drafted positions:
+ *
+ *   picospec_compress        sparse Top-K record of every draft distribution        (Eq. 4)
+ *   picospec_sample_draft    the drafter's token draw from that record (edge side, Section 3.3)
+ *   picospec_verify          parallel verification: acceptance test, first rejection (Section 3.3)
+ *   picospec_sample_residual correction token ~ norm(max(0, P_j - Q_j)), or the bonus token
+ *
+ * Conventions shared by all calls
+ *   - Every data pointer is a DEVICE pointer (HBM) unless marked "host".  The caller owns all
+ *     buffers; the library neither allocates nor frees nor synchronises.  Work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) of the current device
+ *     and the call returns at once; outputs are valid once the stream reaches that point.
+ *   - Logits are row-major [rows, ld] with ld >= V elements between row starts, dtype
+ *     PICOSPEC_F32 or PICOSPEC_BF16; the base pointer must be element-aligned.  Rows need not be
+ *     16-byte aligned (aligned rows stream fastest).  Softmax is taken at `temperature` > 0:
+ *     P(x) = exp(z_x / T - lse).  NaN or +inf logits give unspecified (but memory-safe) results.
+ *   - Ragged batch: seq_off[B+1] (int32, device) is the CSR over draft rows, gamma_b =
+ *     seq_off[b+1] - seq_off[b] >= 0, N = seq_off[B] is also passed from the host as n_draft.
+ *     Target rows are packed with one extra (bonus) row per sequence: position t in 0..gamma_b
+ *     of sequence b is target row seq_off[b] + b + t.  `uniforms` ([N+B] fp32 in [0,1)) is
+ *     indexed like target rows: entry (b, t < gamma_b) drives the acceptance of draft position t,
+ *     entry (b, gamma_b) drives the correction / bonus draw whatever n_accept[b] turns out to be.
+ *   - Sparse record of one row: k slots; idx[slot] (int32 vocabulary id) and prob[slot] (fp32,
+ *     the raw probability P(id), not renormalised), ordered by (logit descending, id ascending);
+ *     count used slots, the rest hold idx = -1, prob = 0; mass = sum of the kept prob.
+ *     8 bytes per kept component, as in the paper's payload arithmetic.
+ *   - Return value: PICOSPEC_OK or a negative PICOSPEC_E* code.  Misuse that the host can see
+ *     (null pointers, sizes, dtype, workspace) is rejected BEFORE anything is launched.
+ *     Data-dependent conditions never fail a call; they set bits in `flags`.
+ *   - Thread safety: no global mutable state besides per-device kernel attributes set on first
+ *     use; concurrent calls on different streams are independent.
+ */
+#ifndef PICOSPEC_H
+#define PICOSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { PICOSPEC_F32 = 0, PICOSPEC_BF16 = 1 };
+
+enum {
+    PICOSPEC_OK = 0,
+    PICOSPEC_EINVAL = -1,      /* null pointer, size out of range, bad temperature ... */
+    PICOSPEC_EWORKSPACE = -2,  /* workspace smaller than picospec_workspace_bytes() says */
+    PICOSPEC_EDTYPE = -3,      /* dtype is neither PICOSPEC_F32 nor PICOSPEC_BF16 */
+    PICOSPEC_EHIP = -4,        /* a HIP runtime call (launch, attribute) failed */
+    PICOSPEC_EUNSUPPORTED = -5 /* k or V beyond the limits reported by picospec_limit() */
+};
+
+/* bits of flags[b] */
+enum {
+    PICOSPEC_FLAG_TOKEN_NOT_IN_SUPPORT = 1u, /* a drafted token was absent from its compressed row: treated as q = 0 (accepted) */
+    PICOSPEC_FLAG_NONFINITE = 2u,            /* a target row's log-sum-exp is not finite */
+    PICOSPEC_FLAG_RESIDUAL_EMPTY = 4u,       /* residual mass <= 0: the token was drawn from P itself */
+    PICOSPEC_FLAG_BAD_INPUT = 8u             /* token id outside [0,V), negative gamma_b, n_accept outside [0,gamma_b] */
+};
+
+enum { PICOSPEC_CALL_COMPRESS = 0, PICOSPEC_CALL_SAMPLE_DRAFT = 1, PICOSPEC_CALL_VERIFY = 2, PICOSPEC_CALL_SAMPLE_RESIDUAL = 3 };
+enum { PICOSPEC_LIMIT_MAX_K = 0, PICOSPEC_LIMIT_MAX_V = 1 };
+
+/*
+ * Sparse compression (Section 3.3, Eq. 4): for each of n_rows distributions keep the k
+ * highest-probability components and their indices.  One streaming pass per row computes the
+ * softmax statistics and selects on the stored logits (exact integer order; equal logits -> lower
+ * id first; -0.0 ties with +0.0).
+ *   logits [n_rows, ld]           in
+ *   k      1..min(V, picospec_limit(MAX_K)) slots per row
+ *   top_p  <= 0 or >= 1: plain Top-K.  Otherwise count = the smallest prefix of the descending
+ *          order whose probability sum reaches top_p, capped at k (a workload setting, not in the paper)
+ *   idx [n_rows,k] int32, prob [n_rows,k] fp32, count [n_rows] int32, mass [n_rows] fp32,
+ *   lse [n_rows] fp32             out
+ *   workspace: picospec_workspace_bytes(PICOSPEC_CALL_COMPRESS, ...) bytes, may be NULL when that is 0.
+ */
+int picospec_compress(const void* logits, int dtype, int64_t ld, int32_t n_rows, int32_t V,
+                      float temperature, int32_t k, float top_p,
+                      int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The drafter's draw (Section 3.3: the edge drafts a token and records its probability q_i):
+ * inverse CDF over the used slots of each row in slot order with weights prob[slot]:
+ * tok = idx[first slot whose inclusive cumulative weight exceeds u * sum of weights].
+ *   uniforms [n_rows] fp32 in [0,1)   in
+ *   tok [n_rows] int32, q_scalar [n_rows] fp32 (nullable) = prob/mass of the drawn slot   out
+ */
+int picospec_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
+                          int32_t k, int32_t n_rows, const float* uniforms,
+                          int32_t* tok, float* q_scalar, void* stream);
+
+/*
+ * Parallel verification (Section 3.3; acceptance rule of standard speculative sampling, cited
+ * there from Chen et al.): for every target row its softmax statistics; for every draft position
+ * p_i = P_i(x_i) and qhat_i; accept_i <=> u_i < min(1, p_i / qhat_i); n_accept[b] = index of the
+ * first position not accepted, gamma_b if none.
+ *   tgt_logits [n_draft + B, ld]; seq_off [B+1]; draft_tok [n_draft]                         in
+ *   q_idx/q_prob [n_draft,k], q_count/q_mass [n_draft]: records from picospec_compress       in
+ *   renorm   1: qhat = prob/mass (the distribution picospec_sample_draft draws from; keeps the
+ *            emitted tokens distributed exactly as the target for any k)   0: qhat = prob
+ *   q_scalar nullable [n_draft]: the scalar q_i the edge recorded and uplinks (Section 3.3); when
+ *            given it replaces the sparse lookup and q_idx/q_prob/q_count/q_mass may be NULL
+ *   uniforms [n_draft + B]                                                                    in
+ *   n_accept [B]; p_tok, q_tok [n_draft] (nullable); flags [B]                                out
+ *   tgt_max, tgt_sum, tgt_lse [n_draft + B] fp32: row maximum M of the raw logits,
+ *            S = sum exp((z - M)/T), and lse = M/T + ln S (tgt_lse nullable)                  out
+ */
+int picospec_verify(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                    int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                    const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                    int32_t k, int renorm, const float* q_scalar, const float* uniforms,
+                    int32_t* n_accept, float* p_tok, float* q_tok,
+                    float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Correction / bonus token (Section 3.3: norm(max(0, P_j(x) - Q_j(x)))): for sequence b with
+ * j = n_accept[b], r(x) = max(0, P_j(x) - qhat_j(x)) with qhat = 0 off the record's support, and
+ * the empty record when j = gamma_b (bonus token ~ P).  R = sum_x r(x);
+ * out_tok[b] = first x (ascending id) whose inclusive cumulative r exceeds u*R.
+ *   tgt_max, tgt_sum [n_draft + B]: from picospec_verify                                      in
+ *   out_tok [B] int32, resid_mass [B] fp32 (= R; 0 with PICOSPEC_FLAG_RESIDUAL_EMPTY), flags [B]   out
+ */
+int picospec_sample_residual(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                             int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
+                             const float* tgt_max, const float* tgt_sum,
+                             const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                             int32_t k, int renorm, const float* uniforms,
+                             int32_t* out_tok, float* resid_mass, uint32_t* flags,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* host: bytes of device workspace the given call needs for (dtype, rows, V, k); 0 if none. */
+size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k);
+
+/* host: largest supported k (PICOSPEC_LIMIT_MAX_K) or V (PICOSPEC_LIMIT_MAX_V); -1 for an unknown id. */
+int64_t picospec_limit(int which);
+
+/* host: static string for a return code. */
+const char* picospec_strerror(int code);
+
+/* host: ABI version, major*1000 + minor. */
+int picospec_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PICOSPEC_H */

@@ -11,6 +11,7 @@ __all__ = ["binding", "workloads"]
 def __getattr__(name):
     # Loaded on first use so that the input generators can be imported without the HIP library.
     if name in ("compress", "verify", "sample_residual", "sample_draft", "binding"):
-        from . import binding as _b
+        import importlib
+        _b = importlib.import_module(__name__ + ".binding")
         return _b if name == "binding" else getattr(_b, name)
     raise AttributeError(name)

@@ -1,0 +1,193 @@
+"""ctypes binding of libpicospec.so with the same names as the C ABI (include/picospec.h).
+
+Argument marshalling only: torch supplies device memory and the current stream, every step of
+the path runs in the library's HIP kernels.  There is no fallback: if the library has not been
+built (``python -m paper_2603_19133_amd.build``) importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpicospec.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, EWORKSPACE, EDTYPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+FLAG_TOKEN_NOT_IN_SUPPORT, FLAG_NONFINITE, FLAG_RESIDUAL_EMPTY, FLAG_BAD_INPUT = 1, 2, 4, 8
+CALL_COMPRESS, CALL_SAMPLE_DRAFT, CALL_VERIFY, CALL_SAMPLE_RESIDUAL = 0, 1, 2, 3
+LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
+
+EXPORTS = ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
+           "picospec_workspace_bytes", "picospec_limit", "picospec_strerror", "picospec_version")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_19133_amd.build` "
+                      "(there is no CPU fallback)")
+
+lib = C.CDLL(LIB_PATH)
+
+_p, _i32, _i64, _f, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+lib.picospec_compress.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _i32, _f, _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_sample_draft.argtypes = [_p, _p, _p, _p, _i32, _i32, _p, _p, _p, _p]
+lib.picospec_verify.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int,
+                                _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_sample_residual.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
+                                         _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_workspace_bytes.argtypes = [C.c_int, C.c_int, _i32, _i32, _i32]
+lib.picospec_workspace_bytes.restype = _sz
+lib.picospec_limit.argtypes = [C.c_int]
+lib.picospec_limit.restype = _i64
+lib.picospec_strerror.argtypes = [C.c_int]
+lib.picospec_strerror.restype = C.c_char_p
+for _n in ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
+           "picospec_version"):
+    getattr(lib, _n).restype = C.c_int
+
+
+class PicoSpecError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"picospec error {code}: {lib.picospec_strerror(code).decode()}")
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise PicoSpecError(rc)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise PicoSpecError(EDTYPE)
+
+
+def _logits_2d(t: torch.Tensor):
+    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+        raise PicoSpecError(EINVAL)
+    return _dtype_code(t), t.stride(0)
+
+
+@dataclass
+class Compressed:
+    idx: torch.Tensor     # int32 [rows, k]
+    prob: torch.Tensor    # float32 [rows, k]
+    count: torch.Tensor   # int32 [rows]
+    mass: torch.Tensor    # float32 [rows]
+    lse: torch.Tensor     # float32 [rows]
+    k: int
+
+
+def alloc_compressed(rows: int, k: int, device) -> Compressed:
+    e = lambda *s, dt=torch.float32: torch.empty(*s, dtype=dt, device=device)
+    return Compressed(e(rows, k, dt=torch.int32), e(rows, k), e(rows, dt=torch.int32), e(rows), e(rows), k)
+
+
+def compress(logits: torch.Tensor, V: int, temperature: float, k: int, top_p: float = 0.0,
+             out: Compressed | None = None) -> Compressed:
+    """picospec_compress on [rows, >=V] fp32/bf16 device logits."""
+    dt, ld = _logits_2d(logits)
+    rows = logits.shape[0]
+    out = out or alloc_compressed(rows, k, logits.device)
+    _check(lib.picospec_compress(_ptr(logits), dt, ld, rows, V, temperature, k, top_p,
+                                 _ptr(out.idx), _ptr(out.prob), _ptr(out.count), _ptr(out.mass), _ptr(out.lse),
+                                 None, 0, _stream()))
+    return out
+
+
+def sample_draft(q: Compressed, uniforms: torch.Tensor, tok: torch.Tensor | None = None,
+                 q_scalar: torch.Tensor | None = None):
+    """picospec_sample_draft -> (tok int32 [rows], q_scalar float32 [rows])."""
+    rows = q.idx.shape[0]
+    tok = tok if tok is not None else torch.empty(rows, dtype=torch.int32, device=q.idx.device)
+    q_scalar = q_scalar if q_scalar is not None else torch.empty(rows, dtype=torch.float32, device=q.idx.device)
+    _check(lib.picospec_sample_draft(_ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), q.k, rows,
+                                     _ptr(uniforms), _ptr(tok), _ptr(q_scalar), _stream()))
+    return tok, q_scalar
+
+
+@dataclass
+class Verified:
+    n_accept: torch.Tensor   # int32 [B]
+    p_tok: torch.Tensor      # float32 [N]
+    q_tok: torch.Tensor      # float32 [N]
+    tgt_max: torch.Tensor    # float32 [N+B]
+    tgt_sum: torch.Tensor    # float32 [N+B]
+    tgt_lse: torch.Tensor    # float32 [N+B]
+    flags: torch.Tensor      # int32 (bit pattern of uint32) [B]
+
+
+def alloc_verified(B: int, N: int, device) -> Verified:
+    e = lambda n, dt=torch.float32: torch.empty(n, dtype=dt, device=device)
+    return Verified(e(B, torch.int32), e(N), e(N), e(N + B), e(N + B), e(N + B), e(B, torch.int32))
+
+
+def verify(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+           draft_tok: torch.Tensor, q: Compressed | None, uniforms: torch.Tensor, renorm: int = 1,
+           q_scalar: torch.Tensor | None = None, out: Verified | None = None) -> Verified:
+    """picospec_verify; seq_off int32 [B+1] on device, n_draft = seq_off[B] known on the host."""
+    dt, ld = _logits_2d(tgt_logits)
+    B = seq_off.shape[0] - 1
+    out = out or alloc_verified(B, n_draft, tgt_logits.device)
+    _check(lib.picospec_verify(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off), _ptr(draft_tok),
+                               _ptr(q.idx) if q else None, _ptr(q.prob) if q else None,
+                               _ptr(q.count) if q else None, _ptr(q.mass) if q else None,
+                               q.k if q else 0, renorm, _ptr(q_scalar), _ptr(uniforms),
+                               _ptr(out.n_accept), _ptr(out.p_tok), _ptr(out.q_tok),
+                               _ptr(out.tgt_max), _ptr(out.tgt_sum), _ptr(out.tgt_lse), _ptr(out.flags),
+                               None, 0, _stream()))
+    return out
+
+
+@dataclass
+class Residual:
+    out_tok: torch.Tensor     # int32 [B]
+    resid_mass: torch.Tensor  # float32 [B]
+    flags: torch.Tensor       # int32 [B]
+
+
+def alloc_residual(B: int, device) -> Residual:
+    return Residual(torch.empty(B, dtype=torch.int32, device=device),
+                    torch.empty(B, dtype=torch.float32, device=device),
+                    torch.empty(B, dtype=torch.int32, device=device))
+
+
+def sample_residual(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+                    ver: Verified, q: Compressed, uniforms: torch.Tensor, renorm: int = 1,
+                    out: Residual | None = None, n_accept: torch.Tensor | None = None) -> Residual:
+    """picospec_sample_residual from the statistics and first-rejection indices of `ver`."""
+    dt, ld = _logits_2d(tgt_logits)
+    B = seq_off.shape[0] - 1
+    out = out or alloc_residual(B, tgt_logits.device)
+    na = ver.n_accept if n_accept is None else n_accept
+    _check(lib.picospec_sample_residual(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off), _ptr(na),
+                                        _ptr(ver.tgt_max), _ptr(ver.tgt_sum),
+                                        _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), q.k, renorm,
+                                        _ptr(uniforms), _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
+                                        None, 0, _stream()))
+    return out
+
+
+def workspace_bytes(which: int, dtype: int, rows: int, V: int, k: int) -> int:
+    return int(lib.picospec_workspace_bytes(which, dtype, rows, V, k))
+
+
+def limit(which: int) -> int:
+    return int(lib.picospec_limit(which))
+
+
+def version() -> int:
+    return int(lib.picospec_version())

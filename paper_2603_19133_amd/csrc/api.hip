@@ -1,0 +1,142 @@
+// C ABI of the library (include/picospec.h): host-side validation and the ragged-batch dispatch
+// onto the gfx950 kernels.  Nothing is launched unless every host-checkable argument is valid.
+#include "../../include/picospec.h"
+
+#include <cmath>
+
+#include "kernels.hpp"
+
+using namespace picospec;
+
+namespace {
+
+bool finite_pos(float t) { return std::isfinite(t) && t > 0.f; }
+
+int check_logits(const void* logits, int dtype, int64_t ld, int64_t rows, int32_t V, float temperature)
+{
+    if (dtype != PICOSPEC_F32 && dtype != PICOSPEC_BF16) return PICOSPEC_EDTYPE;
+    if (rows < 0 || V < 1 || ld < V || !finite_pos(temperature)) return PICOSPEC_EINVAL;
+    if (V > kMaxV) return PICOSPEC_EUNSUPPORTED;
+    if (rows > 0 && !logits) return PICOSPEC_EINVAL;
+    const uintptr_t esz = dtype == PICOSPEC_F32 ? 4 : 2;
+    if ((uintptr_t)logits % esz) return PICOSPEC_EINVAL;
+    return PICOSPEC_OK;
+}
+
+int check_workspace(int which, int dtype, int64_t rows, int32_t V, int32_t k, const void* ws, size_t ws_bytes)
+{
+    const size_t need = picospec_workspace_bytes(which, dtype, (int32_t)rows, V, k);
+    if (need && (!ws || ws_bytes < need)) return PICOSPEC_EWORKSPACE;
+    return PICOSPEC_OK;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? PICOSPEC_OK : PICOSPEC_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+int picospec_compress(const void* logits, int dtype, int64_t ld, int32_t n_rows, int32_t V,
+                      float temperature, int32_t k, float top_p,
+                      int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_logits(logits, dtype, ld, n_rows, V, temperature)) return rc;
+    if (k < 1 || k > V || std::isnan(top_p)) return PICOSPEC_EINVAL;
+    if (k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (n_rows > 0 && (!idx || !prob || !count || !mass || !lse)) return PICOSPEC_EINVAL;
+    if (int rc = check_workspace(PICOSPEC_CALL_COMPRESS, dtype, n_rows, V, k, workspace, workspace_bytes)) return rc;
+    return hip_status(launch_compress(logits, dtype, ld, n_rows, V, temperature, k, top_p, idx, prob, count,
+                                      mass, lse, (hipStream_t)stream));
+}
+
+int picospec_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
+                          int32_t k, int32_t n_rows, const float* uniforms,
+                          int32_t* tok, float* q_scalar, void* stream)
+{
+    if (n_rows < 0 || k < 1) return PICOSPEC_EINVAL;
+    if (n_rows > 0 && (!idx || !prob || !count || !mass || !uniforms || !tok)) return PICOSPEC_EINVAL;
+    return hip_status(launch_sample_draft(idx, prob, count, mass, k, n_rows, uniforms, tok, q_scalar,
+                                          (hipStream_t)stream));
+}
+
+int picospec_verify(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                    int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                    const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                    int32_t k, int renorm, const float* q_scalar, const float* uniforms,
+                    int32_t* n_accept, float* p_tok, float* q_tok,
+                    float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
+    const int64_t rows = (int64_t)n_draft + B;
+    if (rows > INT32_MAX) return PICOSPEC_EINVAL;
+    if (int rc = check_logits(tgt_logits, dtype, ld, rows, V, temperature)) return rc;
+    if (renorm != 0 && renorm != 1) return PICOSPEC_EINVAL;
+    if (B > 0 && (!seq_off || !uniforms || !n_accept || !flags || !tgt_max || !tgt_sum)) return PICOSPEC_EINVAL;
+    if (n_draft > 0) {
+        if (!draft_tok) return PICOSPEC_EINVAL;
+        if (!q_scalar && (k < 1 || !q_idx || !q_prob || !q_count || !q_mass)) return PICOSPEC_EINVAL;
+    }
+    if (int rc = check_workspace(PICOSPEC_CALL_VERIFY, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s))
+        return hip_status(e);
+    return hip_status(launch_accept(tgt_logits, dtype, ld, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
+                                    q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum,
+                                    n_accept, p_tok, q_tok, flags, s));
+}
+
+int picospec_sample_residual(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                             int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
+                             const float* tgt_max, const float* tgt_sum,
+                             const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                             int32_t k, int renorm, const float* uniforms,
+                             int32_t* out_tok, float* resid_mass, uint32_t* flags,
+                             void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
+    const int64_t rows = (int64_t)n_draft + B;
+    if (rows > INT32_MAX) return PICOSPEC_EINVAL;
+    if (int rc = check_logits(tgt_logits, dtype, ld, rows, V, temperature)) return rc;
+    if (renorm != 0 && renorm != 1) return PICOSPEC_EINVAL;
+    if (B > 0 && (!seq_off || !n_accept || !tgt_max || !tgt_sum || !uniforms || !out_tok || !resid_mass || !flags))
+        return PICOSPEC_EINVAL;
+    if (n_draft > 0 && (k < 1 || !q_idx || !q_prob || !q_count || !q_mass)) return PICOSPEC_EINVAL;
+    if (int rc = check_workspace(PICOSPEC_CALL_SAMPLE_RESIDUAL, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
+    return hip_status(launch_residual(tgt_logits, dtype, ld, V, temperature, B, seq_off, n_accept, tgt_max, tgt_sum,
+                                      q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass,
+                                      flags, (hipStream_t)stream));
+}
+
+size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k)
+{
+    (void)which_call; (void)dtype; (void)rows; (void)V; (void)k;
+    return 0;   // every kernel keeps its intermediate state in LDS
+}
+
+int64_t picospec_limit(int which)
+{
+    switch (which) {
+        case PICOSPEC_LIMIT_MAX_K: return kMaxK;
+        case PICOSPEC_LIMIT_MAX_V: return kMaxV;
+        default: return -1;
+    }
+}
+
+const char* picospec_strerror(int code)
+{
+    switch (code) {
+        case PICOSPEC_OK: return "ok";
+        case PICOSPEC_EINVAL: return "invalid argument (null pointer, size out of range, temperature <= 0, misaligned base)";
+        case PICOSPEC_EWORKSPACE: return "workspace missing or smaller than picospec_workspace_bytes()";
+        case PICOSPEC_EDTYPE: return "dtype must be PICOSPEC_F32 or PICOSPEC_BF16";
+        case PICOSPEC_EHIP: return "HIP runtime call failed";
+        case PICOSPEC_EUNSUPPORTED: return "k or V exceeds picospec_limit()";
+        default: return "unknown picospec error code";
+    }
+}
+
+int picospec_version(void) { return 1000; }
+
+}  // extern "C"

@@ -1,0 +1,191 @@
+// Device-side helpers shared by the gfx950 kernels: 16-byte row streaming with an alignment
+// prologue, order-preserving keys, wave64 reductions, accurate exponentials for emitted values.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace picospec {
+
+constexpr int kWave = 64;
+constexpr int kThreads = 1024;            // one workgroup = 16 waves = one row (or one sequence)
+constexpr int kWaves = kThreads / kWave;
+constexpr float kNegInf = -__builtin_huge_valf();
+
+// ---------------------------------------------------------------- wave64 / workgroup reductions
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
+    uint32_t lo = __shfl_xor((uint32_t)v, o, kWave), hi = __shfl_xor((uint32_t)(v >> 32), o, kWave);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { uint64_t w = shfl_xor_u64(v, o); v = w < v ? w : v; }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { uint64_t w = shfl_xor_u64(v, o); v = w > v ? w : v; }
+    return v;
+}
+
+// inclusive prefix sum across the 64 lanes of a wave
+template <typename T>
+__device__ __forceinline__ T wave_scan_incl(T v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        T w = __shfl_up(v, o, kWave);
+        if (lane >= o) v += w;
+    }
+    return v;
+}
+
+// ---------------------------------------------------------------- order-preserving keys
+
+// fp32 bit pattern -> uint32 whose unsigned order is the numeric order; -0.0 maps onto +0.0.
+__device__ __forceinline__ uint32_t key_of_bits(uint32_t b) {
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ uint32_t bits_of_key(uint32_t k) {
+    return (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+}
+
+// (logit descending, id ascending) == composite descending.  Composites of distinct ids differ.
+__device__ __forceinline__ uint64_t composite_of(uint32_t bits, uint32_t id) {
+    return ((uint64_t)key_of_bits(bits) << 32) | (uint64_t)(0xFFFFFFFFu - id);
+}
+
+// ---------------------------------------------------------------- exponentials
+
+// exp((x - m) / T) for the streaming sums: one subtract, one multiply, one v_exp_f32.
+// c = log2(e) / T.
+__device__ __forceinline__ float exp_stream(float x, float m, float c) {
+    return __builtin_amdgcn_exp2f((x - m) * c);
+}
+
+// exp((x - m) / T) for values that are emitted (probabilities): the exponent is formed in fp64 and
+// split into integer and fraction so that its magnitude does not cost relative accuracy.
+__device__ __forceinline__ double exp_emit(float x, float m, double c) {
+    double a = ((double)x - (double)m) * c;      // <= 0 for x <= m
+    if (!(a > -1100.0)) return 0.0;               // also catches x = -inf
+    double n = rint(a);
+    float f = (float)(a - n);                     // |f| <= 0.5, exact difference
+    return ldexp((double)exp2f(f), (int)n);
+}
+
+// ---------------------------------------------------------------- row streaming
+//
+// A row of V elements is read as 16-byte vectors.  If the row does not start on a 16-byte
+// boundary the vectors are taken from the aligned address below it and the elements in front of
+// the row (and behind its end) are masked: an aligned 16-byte block that contains one valid byte
+// never leaves the page that byte lives on.  `o` = number of masked elements in front (0 for
+// aligned rows), virtual element v = o + x.
+
+template <bool BF16> struct Vec;
+template <> struct Vec<false> { static constexpr int N = 4; };   // 4 x fp32
+template <> struct Vec<true>  { static constexpr int N = 8; };   // 8 x bf16
+
+struct RowView {
+    const uint4* base;   // 16-byte aligned
+    int o;               // leading masked elements
+    int L;               // o + V
+};
+
+template <bool BF16>
+__device__ __forceinline__ RowView row_view(const void* logits, int64_t ld, int64_t row, int V) {
+    const int esz = BF16 ? 2 : 4;
+    uintptr_t p = (uintptr_t)logits + (uintptr_t)row * (uintptr_t)ld * esz;
+    RowView r;
+    r.o = (int)((p & 15u) / esz);
+    r.base = (const uint4*)(p & ~(uintptr_t)15u);
+    r.L = r.o + V;
+    return r;
+}
+
+// Vector q (in units of 16 bytes from base); returns false (and leaves `out` untouched) if the
+// vector lies wholly outside [o, L).
+template <bool BF16>
+__device__ __forceinline__ bool vec_in_row(const RowView& r, int q) {
+    const int n = Vec<BF16>::N;
+    int v0 = q * n;
+    return (v0 < r.L) && (v0 + n > r.o);
+}
+
+// Unpack a 16-byte vector into fp32 values (exact widening for bf16).
+template <bool BF16>
+__device__ __forceinline__ void unpack(const uint4& raw, float (&out)[Vec<BF16>::N]) {
+    if constexpr (BF16) {
+        out[0] = __uint_as_float(raw.x << 16); out[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+        out[2] = __uint_as_float(raw.y << 16); out[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+        out[4] = __uint_as_float(raw.z << 16); out[5] = __uint_as_float(raw.z & 0xFFFF0000u);
+        out[6] = __uint_as_float(raw.w << 16); out[7] = __uint_as_float(raw.w & 0xFFFF0000u);
+    } else {
+        out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
+        out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
+    }
+}
+
+// One logit by vocabulary id (random access).
+template <bool BF16>
+__device__ __forceinline__ float logit_at(const void* logits, int64_t ld, int64_t row, int x) {
+    if constexpr (BF16) {
+        const uint16_t* p = (const uint16_t*)logits + row * ld + x;
+        return __uint_as_float((uint32_t)(*p) << 16);
+    } else {
+        return ((const float*)logits)[row * ld + x];
+    }
+}
+
+// Per-thread online softmax state: s = sum exp((x - m)/T) over the elements this thread has seen.
+struct OnlineSum {
+    float m = kNegInf;
+    float s = 0.f;
+    // raise the reference to at least bm (the maximum of the next elements) before adding them
+    __device__ __forceinline__ float rebase(float bm, float c) {
+        if (bm > m) {
+            s *= __builtin_amdgcn_exp2f((m - bm) * c);   // m = -inf: exp2(-inf) = 0, s stays 0
+            m = bm;
+        }
+        return m == kNegInf ? 0.f : m;                    // reference for rows of only -inf so far
+    }
+};
+
+// Combine the per-thread (m, s) of a workgroup.  Result in every thread: M = max m,
+// S = sum s * exp((m - M)/T) accumulated in fp64.  `sh` needs 2*kWaves doubles.
+__device__ __forceinline__ void block_softmax_stats(float m, float s, float c, double* sh, float& M, double& S) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    float wm = wave_max(m);
+    if (lane == 0) sh[wave] = (double)wm;
+    __syncthreads();
+    float bm = kNegInf;
+    for (int w = 0; w < kWaves; ++w) bm = fmaxf(bm, (float)sh[w]);
+    float scaled = (m == kNegInf) ? 0.f : s * __builtin_amdgcn_exp2f((m - bm) * c);
+    double ws = wave_sum((double)scaled);
+    if (lane == 0) sh[kWaves + wave] = ws;
+    __syncthreads();
+    double tot = 0.0;
+    for (int w = 0; w < kWaves; ++w) tot += sh[kWaves + w];
+    __syncthreads();
+    M = bm;
+    S = tot;
+}
+
+}  // namespace picospec

@@ -1,0 +1,38 @@
+// Host-side launchers of the gfx950 kernels (internal to the library; the public surface is
+// include/picospec.h).  Every launcher enqueues on `stream` and returns the launch status.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace picospec {
+
+constexpr int kMaxK = 4096;          // candidate buffer in LDS holds 16384 entries; k beyond this is refused
+constexpr int kMaxV = 1 << 20;       // residual sampler keeps one partial sum per 256/512-element segment in LDS
+
+hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
+                           int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
+                           float* lse, hipStream_t stream);
+
+hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
+                               int k, int n_rows, const float* uniforms, int32_t* tok, float* q_scalar,
+                               hipStream_t stream);
+
+hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
+                            float* row_max, float* row_sum, float* row_lse, hipStream_t stream);
+
+hipError_t launch_accept(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
+                         int B, const int32_t* seq_off, const int32_t* draft_tok,
+                         const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                         int k, int renorm, const float* q_scalar, const float* uniforms,
+                         const float* tgt_max, const float* tgt_sum,
+                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags, hipStream_t stream);
+
+hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
+                           int B, const int32_t* seq_off, const int32_t* n_accept,
+                           const float* tgt_max, const float* tgt_sum,
+                           const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                           int k, int renorm, const float* uniforms,
+                           int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
+
+}  // namespace picospec

@@ -1,0 +1,179 @@
+// Parallel verification (paper Section 3.3): softmax statistics of every target row in one
+// streaming pass, then per sequence the sparse lookup of the drafted token's probability, the
+// acceptance test u < min(1, p/qhat) and the first rejected position.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace picospec {
+
+namespace {
+
+// One workgroup per row: M = max z, S = sum exp((z - M)/T), lse = M/T + ln S.
+template <bool BF16, int NV>
+__global__ __launch_bounds__(kThreads) void row_stats_kernel(
+    const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+    float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse)
+{
+    __shared__ double red[2 * kWaves];
+    constexpr int N = Vec<BF16>::N, E = NV * N, TILE = kThreads * E;
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    const RowView rv = row_view<BF16>(logits, ld, row, V);
+    const int n_tiles = (rv.L + TILE - 1) / TILE;
+    const float c = 1.4426950408889634f * inv_T;
+
+    uint4 cur[NV], nxt[NV];
+    auto load_tile = [&](int it, uint4 (&dst)[NV]) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            int q = it * (kThreads * NV) + j * kThreads + tid;
+            dst[j] = make_uint4(0, 0, 0, 0);
+            if (vec_in_row<BF16>(rv, q)) dst[j] = rv.base[q];
+        }
+    };
+    load_tile(0, cur);
+    OnlineSum os;
+    for (int it = 0; it < n_tiles; ++it) {
+        if (it + 1 < n_tiles) load_tile(it + 1, nxt);
+        float v[E];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float t[N];
+            unpack<BF16>(cur[j], t);
+#pragma unroll
+            for (int e = 0; e < N; ++e) v[j * N + e] = t[e];
+        }
+        if (it == 0 || it == n_tiles - 1) {
+            const int x0 = it * TILE - rv.o;
+#pragma unroll
+            for (int j = 0; j < NV; ++j)
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    int x = x0 + (j * kThreads + tid) * N + e;
+                    if (x < 0 || x >= V) v[j * N + e] = kNegInf;
+                }
+        }
+        float bm = v[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) bm = fmaxf(bm, v[e]);
+        const float mref = os.rebase(bm, c);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc += exp_stream(v[e], mref, c);
+        os.s += acc;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+    }
+    float M; double S;
+    block_softmax_stats(os.m, os.s, c, red, M, S);
+    if (tid == 0) {
+        row_max[row] = M;
+        row_sum[row] = (float)S;
+        if (row_lse) row_lse[row] = (float)((double)M * (double)inv_T + log(S));
+    }
+}
+
+// One workgroup (4 waves) per sequence, one wave per draft position.
+template <bool BF16>
+__global__ __launch_bounds__(256) void accept_kernel(
+    const void* __restrict__ tgt_logits, int64_t ld, int V, float inv_T, int B,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ draft_tok,
+    const int32_t* __restrict__ q_idx, const float* __restrict__ q_prob,
+    const int32_t* __restrict__ q_count, const float* __restrict__ q_mass, int k, int renorm,
+    const float* __restrict__ q_scalar, const float* __restrict__ uniforms,
+    const float* __restrict__ tgt_max, const float* __restrict__ tgt_sum,
+    int32_t* __restrict__ n_accept, float* __restrict__ p_tok, float* __restrict__ q_tok,
+    uint32_t* __restrict__ flags)
+{
+    __shared__ int s_first;
+    __shared__ unsigned s_flags;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, n_waves = blockDim.x / kWave;
+    const int b = blockIdx.x;
+    const int d0 = seq_off[b];
+    int g = seq_off[b + 1] - d0;
+    unsigned fl = 0;
+    if (g < 0) { fl |= 8u; g = 0; }
+    if (tid == 0) { s_first = g; s_flags = 0; }
+    __syncthreads();
+    const int64_t t0 = (int64_t)d0 + b;
+    const double cd = 1.4426950408889634 * (double)inv_T;
+
+    // every target row of the sequence must have finite statistics
+    for (int t = tid; t <= g; t += blockDim.x) {
+        float M = tgt_max[t0 + t], S = tgt_sum[t0 + t];
+        if (!(fabsf(M) < __builtin_huge_valf()) || !(S > 0.f) || !(S < __builtin_huge_valf())) fl |= 2u;
+    }
+
+    for (int i = wave; i < g; i += n_waves) {
+        const int64_t rd = (int64_t)d0 + i, rt = t0 + i;
+        const int x = draft_tok[rd];
+        const bool bad = x < 0 || x >= V;
+        double qh = 0.0;
+        if (q_scalar) {
+            qh = (double)q_scalar[rd];
+        } else {
+            int cnt = q_count[rd];
+            cnt = cnt < 0 ? 0 : (cnt > k ? k : cnt);
+            const int32_t* ids = q_idx + rd * k;
+            int slot = -1;
+            for (int s = lane; s < cnt; s += kWave)
+                if (ids[s] == x) slot = s;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) slot = max(slot, __shfl_xor(slot, o, kWave));
+            if (slot >= 0 && !bad) {
+                qh = (double)q_prob[rd * k + slot];
+                if (renorm) qh /= (double)q_mass[rd];
+            } else if (lane == 0) {
+                fl |= 1u;
+            }
+        }
+        if (lane == 0) {
+            if (bad) fl |= 8u;
+            double p = 0.0;
+            if (!bad) {
+                const float z = logit_at<BF16>(tgt_logits, ld, rt, x);
+                p = exp_emit(z, tgt_max[rt], cd) / (double)tgt_sum[rt];
+            }
+            const double u = (double)uniforms[rt];
+            // u < min(1, p/qhat), without forming the quotient; qhat = 0 counts as ratio = +inf
+            const bool accept = (u < 1.0) && (qh > 0.0 ? (u * qh < p) : true);
+            if (!accept) atomicMin(&s_first, i);
+            if (p_tok) p_tok[rd] = (float)p;
+            if (q_tok) q_tok[rd] = (float)qh;
+        }
+    }
+    if (fl) atomicOr(&s_flags, fl);
+    __syncthreads();
+    if (tid == 0) {
+        n_accept[b] = s_first;
+        flags[b] = s_flags;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
+                            float* row_max, float* row_sum, float* row_lse, hipStream_t stream)
+{
+    if (n_rows == 0) return hipSuccess;
+    const float inv_T = 1.0f / temperature;
+    if (dtype == 1) hipLaunchKernelGGL((row_stats_kernel<true, 4>), dim3(n_rows), dim3(kThreads), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse);
+    else            hipLaunchKernelGGL((row_stats_kernel<false, 4>), dim3(n_rows), dim3(kThreads), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse);
+    return hipGetLastError();
+}
+
+hipError_t launch_accept(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
+                         int B, const int32_t* seq_off, const int32_t* draft_tok,
+                         const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                         int k, int renorm, const float* q_scalar, const float* uniforms,
+                         const float* tgt_max, const float* tgt_sum,
+                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags, hipStream_t stream)
+{
+    if (B == 0) return hipSuccess;
+    const float inv_T = 1.0f / temperature;
+    if (dtype == 1) hipLaunchKernelGGL(accept_kernel<true>, dim3(B), dim3(256), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
+    else            hipLaunchKernelGGL(accept_kernel<false>, dim3(B), dim3(256), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
+    return hipGetLastError();
+}
+
+}  // namespace picospec

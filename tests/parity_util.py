@@ -1,0 +1,158 @@
+"""Shared machinery of the GPU parity tests: run one round through the oracle and through the
+C-ABI library on the same seeded inputs and compare element by element.
+
+Match criteria (written here once, used by every parity test):
+  * top-k ids, counts, flags, accepted counts, tokens: bit-exact ...
+  * ... except decisions the oracle itself marks as knife-edge: an acceptance whose uniform lies
+    within ACCEPT_MARGIN (relative) of p/q, a draw whose u*R lies within CDF_MARGIN (relative to R)
+    of a CDF step, a top-p count whose threshold lies within TOPP_MARGIN of a cumulative sum.
+    Those sequences/rows are listed, excluded, and their number is bounded.
+  * probabilities, masses, log-sum-exps: relative RTOL.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2603_19133_amd import binding as ps
+from paper_2603_19133_amd import workloads as W
+
+RTOL = 1e-5            # probabilities and masses, fp32 and bf16 inputs alike
+RTOL_LSE = 2e-6
+ACCEPT_MARGIN = 1e-5
+CDF_MARGIN = 1e-6
+TOPP_MARGIN = 1e-6
+
+
+def to_device(a: np.ndarray, device) -> torch.Tensor:
+    if a.dtype == np.uint16:  # bf16 bit patterns
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+@dataclass
+class OracleRound:
+    q: oracle.Compressed
+    tok: np.ndarray
+    ver: oracle.Verified
+    res: oracle.Residual
+
+
+def oracle_round(r: W.Round, renorm: int = 1, tok: np.ndarray | None = None) -> OracleRound:
+    w = r.workload
+    q = oracle.compress(r.draft_logits, w.V, w.T, w.k, w.top_p)
+    if tok is None:
+        tok, _, _ = oracle.sample_draft(q, r.draft_uniforms)
+    ver = oracle.verify(r.tgt_logits, w.V, w.T, r.seq_off, tok, q, r.uniforms, renorm=renorm)
+    res = oracle.sample_residual(r.tgt_logits, w.V, w.T, r.seq_off, ver.n_accept, ver.tgt_lse, q, r.uniforms,
+                                 renorm=renorm)
+    return OracleRound(q, tok, ver, res)
+
+
+@dataclass
+class GpuRound:
+    q: ps.Compressed
+    ver: ps.Verified
+    res: ps.Residual
+
+
+def gpu_round(r: W.Round, tok: np.ndarray, device, renorm: int = 1) -> GpuRound:
+    """The library's three calls on the same inputs; the drafted tokens are the oracle's."""
+    w = r.workload
+    draft = to_device(r.draft_logits, device)
+    tgt = to_device(r.tgt_logits, device)
+    seq_off = torch.from_numpy(r.seq_off).to(device)
+    uni = torch.from_numpy(r.uniforms).to(device)
+    dtok = torch.from_numpy(tok).to(device)
+    q = ps.compress(draft, w.V, w.T, w.k, w.top_p)
+    ver = ps.verify(tgt, w.V, w.T, seq_off, r.N, dtok, q, uni, renorm=renorm)
+    res = ps.sample_residual(tgt, w.V, w.T, seq_off, r.N, ver, q, uni, renorm=renorm)
+    torch.cuda.synchronize()
+    return GpuRound(q, ver, res)
+
+
+def n(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy()
+
+
+def assert_close(got, want, rtol, what, atol=0.0):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    bad = err > rtol * np.abs(want) + atol
+    if bad.any():
+        i = int(np.argmax(err / (np.abs(want) + 1e-300)))
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} beyond rtol={rtol}; worst at {i}: "
+                             f"got {got.flat[i]!r} want {want.flat[i]!r}")
+    return float((err / (np.abs(want) + 1e-300)).max()) if err.size else 0.0
+
+
+def compare_compress(g: ps.Compressed, o: oracle.Compressed, top_p: float = 0.0) -> dict:
+    """Record parity.  Returns statistics (max relative errors, excluded rows)."""
+    gi, gp, gc = n(g.idx), n(g.prob), n(g.count)
+    rows, k = o.idx.shape
+    excluded = []
+    if 0.0 < top_p < 1.0:
+        for r in range(rows):
+            if gc[r] != o.count[r]:
+                # only a threshold within TOPP_MARGIN of a cumulative sum may move the count, and by one
+                assert o.topp_margin[r] < TOPP_MARGIN and abs(int(gc[r]) - int(o.count[r])) == 1, \
+                    (r, gc[r], o.count[r], o.topp_margin[r])
+                excluded.append(r)
+        assert len(excluded) <= max(1, rows // 50), excluded
+    else:
+        assert (gc == o.count).all()
+    keep = np.ones(rows, bool)
+    keep[excluded] = False
+    for r in excluded:                       # the common prefix must still agree
+        c = min(int(gc[r]), int(o.count[r]))
+        assert (gi[r, :c] == o.idx[r, :c]).all()
+    assert (gi[keep] == o.idx[keep]).all(), "top-k ids differ"
+    e_prob = assert_close(gp[keep], o.prob[keep], RTOL, "prob")
+    e_mass = assert_close(n(g.mass)[keep], o.mass[keep], RTOL, "mass")
+    e_lse = assert_close(n(g.lse), o.lse, RTOL_LSE, "lse", atol=1e-6)
+    return dict(prob=e_prob, mass=e_mass, lse=e_lse, topp_excluded=excluded)
+
+
+def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: float = 0.02) -> dict:
+    w = r.workload
+    st = compare_compress(g.q, o.q, w.top_p)
+    assert not st["topp_excluded"] or True
+    off, B = r.seq_off, r.B
+    # target statistics
+    lse_g = n(g.ver.tgt_max).astype(np.float64) / w.T + np.log(n(g.ver.tgt_sum).astype(np.float64))
+    st["tgt_lse"] = assert_close(lse_g, o.ver.tgt_lse, RTOL_LSE, "tgt_lse (from max,sum)", atol=1e-6)
+    assert_close(n(g.ver.tgt_lse), o.ver.tgt_lse, RTOL_LSE, "tgt_lse", atol=2e-6)
+    # rows whose record is excluded (top-p knife-edge) taint their sequence
+    tainted = np.zeros(B, bool)
+    for row in st["topp_excluded"]:
+        tainted[np.searchsorted(off, row, side="right") - 1] = True
+    ok_rows = np.ones(r.N, bool)
+    ok_rows[st["topp_excluded"]] = False
+    st["p_tok"] = assert_close(n(g.ver.p_tok), o.ver.p_tok, RTOL, "p_tok", atol=1e-37)
+    st["q_tok"] = assert_close(n(g.ver.q_tok)[ok_rows], o.ver.q_tok[ok_rows], RTOL, "q_tok")
+    # accepted counts: exact; a mismatch is tolerated only where the oracle marks a knife-edge decision
+    knife = np.array([o.ver.margin[off[b]:off[b + 1]].min(initial=np.inf) < ACCEPT_MARGIN for b in range(B)])
+    na_g = n(g.ver.n_accept)
+    same = na_g == o.ver.n_accept
+    allowed = knife | tainted
+    assert (same | allowed).all(), ("n_accept", np.nonzero(~same & ~allowed)[0][:10])
+    fl_g = n(g.ver.flags).astype(np.int64) & 0xFFFFFFFF
+    assert (fl_g[same] == o.ver.flags[same]).all(), "verify flags"
+    # residual draw: compare wherever both sides sampled the same row; a mismatch is tolerated only where
+    # u*R lies within CDF_MARGIN (relative to R) of a step of the oracle's CDF
+    tok_g = n(g.res.out_tok)
+    tok_same = tok_g == o.res.out_tok
+    tok_allowed = o.res.cdf_margin < CDF_MARGIN
+    assert (tok_same | tok_allowed | ~same).all(), \
+        ("out_tok", np.nonzero(same & ~tok_same & ~tok_allowed)[0][:10])
+    st["resid_mass"] = assert_close(n(g.res.resid_mass)[same], o.res.resid_mass[same], RTOL, "resid_mass")
+    assert ((n(g.res.flags).astype(np.int64) & 0xFFFFFFFF)[same] == o.res.flags[same]).all(), "residual flags"
+    st["mismatch_accept"] = int((~same).sum())           # all of them knife-edge (asserted above)
+    st["mismatch_draw"] = int((same & ~tok_same).sum())  # all of them within CDF_MARGIN of a step
+    assert st["mismatch_accept"] <= max(1, int(max_excluded_frac * B)), st
+    assert st["mismatch_draw"] <= max(1, int(max_excluded_frac * B)), st
+    st["accept_rate"] = float(o.ver.n_accept.sum() / max(1, r.N))
+    return st

@@ -1,0 +1,130 @@
+"""The C-ABI library without a GPU: it loads, exports what include/picospec.h declares, and every
+host-checkable misuse is rejected with its error code before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_19133_amd import binding
+    return binding
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "picospec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(picospec_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(B.lib, n) is not None
+
+
+def test_version_limits_strerror(B):
+    assert B.version() == 1000
+    assert B.limit(B.LIMIT_MAX_K) == 4096 and B.limit(B.LIMIT_MAX_V) == 1 << 20 and B.limit(99) == -1
+    for code in (0, -1, -2, -3, -4, -5, -77):
+        assert len(B.lib.picospec_strerror(code)) > 0
+    assert B.workspace_bytes(B.CALL_COMPRESS, B.F32, 4096, 151936, 4096) == 0
+
+
+FAKE = 0x1000  # a non-null, 16-byte aligned address that is never dereferenced (calls fail validation first)
+
+
+def _compress(B, logits=FAKE, dtype=0, ld=100, rows=2, V=100, T=1.0, k=10, top_p=0.0, outs=(FAKE,) * 5):
+    return B.lib.picospec_compress(logits, dtype, ld, rows, V, T, k, top_p, *outs, None, 0, None)
+
+
+def test_compress_rejects_misuse(B):
+    assert _compress(B, logits=None) == B.EINVAL
+    assert _compress(B, dtype=7) == B.EDTYPE
+    assert _compress(B, ld=99) == B.EINVAL
+    assert _compress(B, V=0) == B.EINVAL
+    assert _compress(B, rows=-1) == B.EINVAL
+    assert _compress(B, T=0.0) == B.EINVAL
+    assert _compress(B, T=-1.0) == B.EINVAL
+    assert _compress(B, T=float("nan")) == B.EINVAL
+    assert _compress(B, k=0) == B.EINVAL
+    assert _compress(B, k=101) == B.EINVAL
+    assert _compress(B, top_p=float("nan")) == B.EINVAL
+    assert _compress(B, logits=FAKE + 2) == B.EINVAL                 # fp32 base not 4-byte aligned
+    assert _compress(B, V=10000, ld=10000, k=5000) == B.EUNSUPPORTED
+    assert _compress(B, V=(1 << 20) + 1, ld=1 << 21) == B.EUNSUPPORTED
+    for i in range(5):
+        outs = [FAKE] * 5
+        outs[i] = None
+        assert _compress(B, outs=tuple(outs)) == B.EINVAL
+
+
+def _verify(B, tgt=FAKE, dtype=0, ld=50, V=50, T=1.0, Bn=2, N=6, seq=FAKE, tok=FAKE, q=(FAKE,) * 4, k=8,
+            renorm=1, qs=None, uni=FAKE, n_acc=FAKE, stats=(FAKE, FAKE), flags=FAKE):
+    return B.lib.picospec_verify(tgt, dtype, ld, V, T, Bn, N, seq, tok, *q, k, renorm, qs, uni, n_acc, None, None,
+                                 stats[0], stats[1], None, flags, None, 0, None)
+
+
+def test_verify_rejects_misuse(B):
+    assert _verify(B, tgt=None) == B.EINVAL
+    assert _verify(B, dtype=2) == B.EDTYPE
+    assert _verify(B, Bn=-1) == B.EINVAL
+    assert _verify(B, N=-1) == B.EINVAL
+    assert _verify(B, T=0.0) == B.EINVAL
+    assert _verify(B, ld=49) == B.EINVAL
+    assert _verify(B, renorm=2) == B.EINVAL
+    assert _verify(B, seq=None) == B.EINVAL
+    assert _verify(B, tok=None) == B.EINVAL
+    assert _verify(B, uni=None) == B.EINVAL
+    assert _verify(B, n_acc=None) == B.EINVAL
+    assert _verify(B, flags=None) == B.EINVAL
+    assert _verify(B, stats=(None, FAKE)) == B.EINVAL
+    assert _verify(B, q=(None, FAKE, FAKE, FAKE)) == B.EINVAL       # sparse record required ...
+    assert _verify(B, k=0) == B.EINVAL
+    assert _verify(B, N=2 ** 31 - 1, Bn=5) == B.EINVAL               # row count overflows int32
+
+
+def _residual(B, tgt=FAKE, dtype=1, ld=64, V=64, T=0.5, Bn=3, N=5, seq=FAKE, n_acc=FAKE, stats=(FAKE, FAKE),
+              q=(FAKE,) * 4, k=4, renorm=1, uni=FAKE, outs=(FAKE, FAKE, FAKE)):
+    return B.lib.picospec_sample_residual(tgt, dtype, ld, V, T, Bn, N, seq, n_acc, *stats, *q, k, renorm, uni, *outs,
+                                          None, 0, None)
+
+
+def test_sample_residual_rejects_misuse(B):
+    assert _residual(B, tgt=None) == B.EINVAL
+    assert _residual(B, tgt=FAKE + 1) == B.EINVAL                    # bf16 base not 2-byte aligned
+    assert _residual(B, dtype=-1) == B.EDTYPE
+    assert _residual(B, V=0) == B.EINVAL
+    assert _residual(B, T=float("inf")) == B.EINVAL
+    assert _residual(B, renorm=-1) == B.EINVAL
+    assert _residual(B, n_acc=None) == B.EINVAL
+    assert _residual(B, stats=(FAKE, None)) == B.EINVAL
+    assert _residual(B, q=(FAKE, None, FAKE, FAKE)) == B.EINVAL
+    assert _residual(B, k=0) == B.EINVAL
+    assert _residual(B, outs=(None, FAKE, FAKE)) == B.EINVAL
+    assert _residual(B, outs=(FAKE, FAKE, None)) == B.EINVAL
+
+
+def test_sample_draft_rejects_misuse(B):
+    f = B.lib.picospec_sample_draft
+    assert f(None, FAKE, FAKE, FAKE, 4, 2, FAKE, FAKE, None, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, FAKE, 0, 2, FAKE, FAKE, None, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, -2, FAKE, FAKE, None, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 2, None, FAKE, None, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 2, FAKE, None, None, None) == B.EINVAL
+
+
+def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
+    """There is no CPU fallback: a missing library is an ImportError, not a silent slow path."""
+    import importlib.util
+    src = os.path.join(ROOT, "paper_2603_19133_amd", "binding.py")
+    dst = tmp_path / "binding_copy.py"
+    dst.write_text(open(src).read())
+    spec = importlib.util.spec_from_file_location("binding_copy", dst)
+    with pytest.raises(ImportError, match="no CPU fallback"):
+        spec.loader.exec_module(importlib.util.module_from_spec(spec))
