@@ -112,12 +112,24 @@ struct RowView {
 template <bool BF16>
 __device__ __forceinline__ RowView row_view(const void* logits, int64_t ld, int64_t row, int V) {
     const int esz = BF16 ? 2 : 4;
-    uintptr_t p = (uintptr_t)logits + (uintptr_t)row * (uintptr_t)ld * esz;
+    const int64_t byte_off = row * ld * esz;
+    const int mis = (int)(((uintptr_t)logits + (uintptr_t)byte_off) & 15u);
     RowView r;
-    r.o = (int)((p & 15u) / esz);
-    r.base = (const uint4*)(p & ~(uintptr_t)15u);
+    r.o = mis / esz;
+    r.base = (const uint4*)((const char*)logits + (byte_off - mis));   // pointer arithmetic keeps the global address space
     r.L = r.o + V;
     return r;
+}
+
+// Bit e of the result is set iff element e of vector q lies inside the row.
+template <bool BF16>
+__device__ __forceinline__ unsigned vec_valid_mask(const RowView& r, int q) {
+    const int n = Vec<BF16>::N;
+    const int x = q * n - r.o;                  // id of the vector's element 0
+    const int lo = x < 0 ? (x < -n ? n : -x) : 0;
+    const int V = r.L - r.o;
+    const int hi = V - x < 0 ? 0 : (V - x > n ? n : V - x);
+    return hi > lo ? (((1u << hi) - 1u) & ~((1u << lo) - 1u)) : 0u;
 }
 
 // Vector q (in units of 16 bytes from base); returns false (and leaves `out` untouched) if the
