@@ -180,24 +180,35 @@ struct OnlineSum {
     }
 };
 
-// Combine the per-thread (m, s) of a workgroup.  Result in every thread: M = max m,
-// S = sum s * exp((m - M)/T) accumulated in fp64.  `sh` needs 2*kWaves doubles.
+// Combine the per-thread (m, s) of a workgroup of WAVES waves.  Result in every thread: M = max m,
+// S = sum s * exp((m - M)/T) accumulated in fp64.  `sh` needs 2*WAVES doubles.
+template <int WAVES = kWaves>
 __device__ __forceinline__ void block_softmax_stats(float m, float s, float c, double* sh, float& M, double& S) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     float wm = wave_max(m);
     if (lane == 0) sh[wave] = (double)wm;
     __syncthreads();
     float bm = kNegInf;
-    for (int w = 0; w < kWaves; ++w) bm = fmaxf(bm, (float)sh[w]);
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) bm = fmaxf(bm, (float)sh[w]);
     float scaled = (m == kNegInf) ? 0.f : s * __builtin_amdgcn_exp2f((m - bm) * c);
     double ws = wave_sum((double)scaled);
-    if (lane == 0) sh[kWaves + wave] = ws;
+    if (lane == 0) sh[WAVES + wave] = ws;
     __syncthreads();
     double tot = 0.0;
-    for (int w = 0; w < kWaves; ++w) tot += sh[kWaves + w];
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) tot += sh[WAVES + w];
     __syncthreads();
     M = bm;
     S = tot;
+}
+
+// Largest float below x (x finite or +inf); -inf stays -inf.  x >= t  <=>  x > float_below(t) for non-NaN x.
+__device__ __forceinline__ float float_below(float t) {
+    uint32_t b = __float_as_uint(t);
+    if (t == kNegInf) return t;
+    if ((b << 1) == 0u) return __uint_as_float(0x80000001u);   // +-0 -> smallest negative subnormal
+    return __uint_as_float((b & 0x80000000u) ? b + 1u : b - 1u);
 }
 
 }  // namespace picospec
