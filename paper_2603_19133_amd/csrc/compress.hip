@@ -43,7 +43,8 @@ static_assert(kMaxV <= (1 << kIdBits), "id field of the composite key");
 static_assert(kCap <= 65536 && kCap / 2 * 2 <= kBins * 4, "a prune keeps a 16-bit index list in the histogram");
 
 struct __align__(16) CompressShared {
-    uint2 cand[kCap];                       // (fp32 bit pattern, id); the sort reuses it as uint64 regions
+    unsigned cand_val[kCap];                // candidates: fp32 bit pattern ...
+    unsigned cand_id[kCap];                 // ... and vocabulary id (the sort reuses both arrays as uint64 regions)
     unsigned hist[kBins];
     double red[2 * kW];
     int wtot[kW];
@@ -113,7 +114,7 @@ __device__ __forceinline__ uint64_t select_threshold(CompressShared& sh, int n, 
         for (int j = 0; j < kPer; ++j) {
             const int i = tid + j * kT;
             if (i < n) {
-                const uint64_t d = composite<BF16>(sh.cand[i]) - lo;   // below the window wraps to >= 2^63
+                const uint64_t d = composite<BF16>(make_uint2(sh.cand_val[i], sh.cand_id[i])) - lo;   // below the window wraps to >= 2^63
                 if ((d >> wbits) == 0) atomicAdd(&sh.hist[kBins - 1 - (int)(d >> shift)], 1u);   // reversed: descending
             }
         }
@@ -153,7 +154,7 @@ __device__ __forceinline__ float prune_to(CompressShared& sh, int n, int target,
 #pragma unroll 4
         for (int j = 0; j < kPer; ++j) {
             const int i = tid + j * kT;
-            if (i < n) mine += composite<BF16>(sh.cand[i]) >= T ? 1 : 0;
+            if (i < n) mine += composite<BF16>(make_uint2(sh.cand_val[i], sh.cand_id[i])) >= T ? 1 : 0;
         }
         mine = wave_sum(mine);
         if (lane == 0) sh.wtot[wave] = mine;
@@ -172,7 +173,7 @@ __device__ __forceinline__ float prune_to(CompressShared& sh, int n, int target,
         const int i = tid + j * kT;
         bool hole = false;
         if (i < n) {
-            const uint2 e = sh.cand[i];
+            const uint2 e = make_uint2(sh.cand_val[i], sh.cand_id[i]);
             const bool kept = composite<BF16>(e) >= T;
             if (kept) { const unsigned key = key_of_bits(e.x); mk = key < mk ? key : mk; }
             hole = !kept && i < target;
@@ -195,7 +196,7 @@ __device__ __forceinline__ float prune_to(CompressShared& sh, int n, int target,
         bool fill = false;
         uint2 e = make_uint2(0, 0);
         if (i >= target && i < n) {
-            e = sh.cand[i];
+            e = make_uint2(sh.cand_val[i], sh.cand_id[i]);
             fill = composite<BF16>(e) >= T;
         }
         const unsigned long long fm = __ballot(fill);
@@ -203,7 +204,7 @@ __device__ __forceinline__ float prune_to(CompressShared& sh, int n, int target,
             int base = 0;
             if (lane == 0) base = atomicAdd(&sh.n_fills, __popcll(fm));
             base = __shfl(base, 0, kWave);
-            if (fill) sh.cand[holes[base + __popcll(fm & below)]] = e;
+            if (fill) { const int h = holes[base + __popcll(fm & below)]; sh.cand_val[h] = e.x; sh.cand_id[h] = e.y; }
         }
     }
     unsigned tk = 0xFFFFFFFFu;
@@ -237,7 +238,7 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
 template <bool BF16>
 __device__ __forceinline__ const uint64_t* sort_candidates(CompressShared& sh, int n, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x;
-    uint64_t* out = reinterpret_cast<uint64_t*>(sh.cand);
+    uint64_t* out = reinterpret_cast<uint64_t*>(sh.cand_val);
     uint64_t* tmp = out + kMaxK;
     const uint64_t lo = (uint64_t)key_lo << kIdBits;
     const uint64_t range = (((uint64_t)key_hi << kIdBits) | kIdMask) - lo;
@@ -254,7 +255,7 @@ __device__ __forceinline__ const uint64_t* sort_candidates(CompressShared& sh, i
         const int i = tid + j * kT;
         c[j] = 0; rbin[j] = 0; arrival[j] = 0;
         if (i < n) {
-            c[j] = composite<BF16>(sh.cand[i]);
+            c[j] = composite<BF16>(make_uint2(sh.cand_val[i], sh.cand_id[i]));
             rbin[j] = kBins - 1 - (int)((c[j] - lo) >> shift);
             arrival[j] = (int)atomicAdd(&sh.hist[rbin[j]], 1u);
         }
@@ -328,13 +329,11 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
     const float c = 1.4426950408889634f * inv_T;
 
     uint4 cur[NV], nxt[NV];
+    const int nq = (rv.L + N - 1) / N;           // 16-byte vectors that overlap the row
     auto load_tile = [&](int it, uint4 (&dst)[NV]) {
+        // vectors behind the row's last one re-read that last vector (always a valid address); unpack_tile masks them
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int q = it * (kT * NV) + j * kT + tid;
-            dst[j] = make_uint4(0, 0, 0, 0);
-            if (vec_in_row<BF16>(rv, q)) dst[j] = rv.base[q];
-        }
+        for (int j = 0; j < NV; ++j) dst[j] = rv.base[min(it * (kT * NV) + j * kT + tid, nq - 1)];
     };
     // unpack a tile; elements outside the row (alignment prologue, tail) become -inf
     auto unpack_tile = [&](int it, const uint4 (&src)[NV], float (&v)[E]) {
@@ -390,7 +389,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
 #pragma unroll
                 for (int e = 0; e < N; ++e) {
                     const int x = (j * kT + tid) * N + e - rv.o;
-                    if (x >= 0 && x < n0) sh.cand[x] = make_uint2(__float_as_uint(v[j * N + e]), (unsigned)x);
+                    if (x >= 0 && x < n0) { sh.cand_val[x] = __float_as_uint(v[j * N + e]); sh.cand_id[x] = (unsigned)x; }
                 }
             // key range of the tile (masked elements are -inf, which only widens it)
             const float wmax = wave_max(bm), wmin = -wave_max(-bn);
@@ -432,29 +431,31 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
             for (;;) {
                 if (pending) {
                     // one ballot per element column: which lanes hold a candidate there
-                    unsigned long long pm[E];
                     int total = 0;
 #pragma unroll
-                    for (int e = 0; e < E; ++e) { pm[e] = __ballot(v[e] > tau_adm); total += __popcll(pm[e]); }
+                    for (int e = 0; e < E; ++e) total += __popcll(__ballot(v[e] > tau_adm));
                     if (total > 0) {
                         int base = 0;
                         if (lane == 0) base = atomicAdd(&sh.cnt, total);
                         base = __builtin_amdgcn_readfirstlane(base);
                         if (base + total <= kCap) {
                             int run = base;
+                            float tau_keep = tau_adm;
+                            asm volatile("" : "+v"(tau_keep));
 #pragma unroll
                             for (int j = 0; j < NV; ++j)
 #pragma unroll
                                 for (int e = 0; e < N; ++e) {
-                                    const unsigned long long m = pm[j * N + e];
-                                    if (m) {
-                                        const int pos = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
-                                                            __builtin_amdgcn_mbcnt_lo((unsigned)m, (unsigned)run));
-                                        if (v[j * N + e] > tau_adm)
-                                            sh.cand[pos] = make_uint2(__float_as_uint(v[j * N + e]),
-                                                                      (unsigned)(x0 + j * kT * N + e));
-                                        run += __popcll(m);
+                                    // the lane masks are formed again rather than kept: sixteen of them would not fit the scalar file
+                                    const bool pass = v[j * N + e] > tau_keep;
+                                    const unsigned long long m = __ballot(pass);
+                                    const int pos = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo((unsigned)m, (unsigned)run));
+                                    if (pass) {
+                                        sh.cand_val[pos] = __float_as_uint(v[j * N + e]);
+                                        sh.cand_id[pos] = (unsigned)(x0 + j * kT * N + e);
                                     }
+                                    run += __popcll(m);
                                 }
                             pending = false;
                         } else if (lane == 0) {
