@@ -3,22 +3,25 @@
 // per row.
 //
 // Streaming selection.  A row is read in tiles of 16-byte vectors (8192 elements per tile).
-//   * Tile 0 is copied whole into a candidate buffer in LDS.  A radix select (11-bit digits, LDS
-//     histogram) on the composite key
-//         (order-preserving logit key) << 20 | (2^20 - 1 - id)
-//     (descending composite == logit descending, id ascending) cuts it down and yields a threshold.
-//   * Optimistic mode: the cut keeps the r largest of tile 0, r chosen so that about 1.3 k elements
-//     of the whole row are expected at or above the r-th value (z = 4.5 sigma above k for
-//     exchangeable rows).  Later tiles append every element >= that value.  If the row ends with
-//     at least k candidates the exact top k is among them (nothing at or above the threshold was
-//     dropped) and one final select finishes the job.
-//   * Safe mode: the cut keeps the k largest seen so far; later elements must be strictly larger
-//     than the k-th (rows are streamed in ascending id, so equal logits that come later lose).
-//     Whenever the buffer would overflow it is pruned back to the exact top k, in either mode,
-//     which also switches to safe mode.  A row whose optimistic threshold was too high (fewer
-//     than k candidates at the end) is streamed again in safe mode.
-//   * The k survivors are ordered by a histogram rank sort, their probabilities formed from the
-//     row's (max, sum), and the record written once.
+//   * Tile 0 stays in registers while a two-pass radix histogram over its order-preserving logit
+//     keys finds a threshold: a value with at least r of the tile's elements at or above it.
+//   * Optimistic pass: r is chosen so that about k + 4.5 sqrt(k) + 20 elements of the whole row are
+//     expected at or above the threshold (for exchangeable rows).  Every element of the row at
+//     or above it -- tile 0 included -- is appended to a candidate buffer in LDS (value, id).
+//     If the row ends with at least k candidates, the exact top k is among them, because nothing
+//     at or above the threshold was dropped.  Waves run free in this pass; a reservation that
+//     does not fit the buffer, or fewer than k candidates at the end, gives the pass up.
+//   * Safe pass (only after a failed optimistic pass, or when the optimistic rank would not pay):
+//     r = k, so the threshold is at or below the k-th largest of tile 0.  The waves meet after
+//     every tile; when the buffer is full it is pruned to the exact top k of everything seen, and
+//     from then on an element must be strictly larger than the k-th (rows are streamed in
+//     ascending id, so equal logits that come later lose the tie).
+//   * The survivors are cut to exactly k by a radix select on the key, ties at the k-th key cut by
+//     a radix select on the id (lower id wins), ordered by a histogram rank sort on the composite
+//         (key << 20) | (2^20 - 1 - id)
+//     their probabilities formed from the row's (max, sum), and the record written once.
+#include <type_traits>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -28,10 +31,9 @@ namespace {
 
 constexpr int kT = 512;                     // threads per workgroup (8 waves)
 constexpr int kW = kT / kWave;
-constexpr int kCap = 8192;                  // candidate slots in LDS (8 bytes each)
-constexpr int kPer = kCap / kT;             // candidates per thread during a select
+constexpr int kCap = 8192;                  // candidate slots in LDS (value + id, 8 bytes)
 constexpr int kBinsLog2 = 11;
-constexpr int kBins = 1 << kBinsLog2;       // histogram bins of the radix select / rank sort
+constexpr int kBins = 1 << kBinsLog2;       // histogram bins of the radix selects / rank sort
 constexpr int kBinsPer = kBins / kT;
 constexpr int kIdBits = 20;                 // ids < 2^20 (kMaxV)
 constexpr unsigned kIdMask = (1u << kIdBits) - 1u;
@@ -51,10 +53,11 @@ struct __align__(16) CompressShared {
     unsigned wkey[2 * kW];
     int cnt;                                // candidates held
     int n_holes, n_fills;                   // compaction of a prune
-    int piv_rbin, piv_above, piv_count;     // radix-select broadcast
+    int piv_bin, piv_before, piv_count;     // radix-select broadcast
     int maxbin;
-    int epoch_overflow[3];                  // per attempt epoch: some wave did not fit
-    int epoch_valid[3];                     // per attempt epoch: first reservation that did not fit
+    int overflowed;                         // optimistic pass: a reservation did not fit
+    int epoch_overflow[3];                  // safe pass, per attempt epoch: some wave did not fit
+    int epoch_valid[3];                     // safe pass, per attempt epoch: first reservation that did not fit
 };
 
 static_assert(sizeof(CompressShared) <= 80 * 1024, "two workgroups share the 160 KB of LDS of a gfx950 CU");
@@ -66,25 +69,30 @@ __device__ __forceinline__ uint32_t short_key(uint32_t bits) {
     return key;
 }
 
+template <bool BF16>
+__device__ __forceinline__ uint32_t bits_of_short_key(uint32_t key) {
+    if constexpr (BF16) key = (key << 16) | ((key & 0x8000u) ? 0u : 0xFFFFu);   // keys of negative values end in ones
+    return bits_of_key(key);
+}
+
 // Composite key; for bf16 rows the key field is 16 bits wide so that no dead bits sit between
 // the logit and the id.
 template <bool BF16>
-__device__ __forceinline__ uint64_t composite(uint2 e) {
-    return ((uint64_t)short_key<BF16>(e.x) << kIdBits) | (uint64_t)(kIdMask - e.y);
+__device__ __forceinline__ uint64_t composite(uint32_t bits, uint32_t id) {
+    return ((uint64_t)short_key<BF16>(bits) << kIdBits) | (uint64_t)(kIdMask - id);
 }
 
-template <bool BF16>
-__device__ __forceinline__ uint2 entry_of(uint64_t c) {
-    uint32_t key = (uint32_t)(c >> kIdBits);
-    if constexpr (BF16) key = (key << 16) | ((key & 0x8000u) ? 0u : 0xFFFFu);   // keys of negative values end in ones
-    return make_uint2(bits_of_key(key), kIdMask - ((uint32_t)c & kIdMask));
+__device__ __forceinline__ void zero_hist(CompressShared& sh) {
+#pragma unroll
+    for (int j = 0; j < kBinsPer; ++j) sh.hist[threadIdx.x + j * kT] = 0;
 }
 
-// Exclusive prefix sum over the kBins counters in sh.hist, each thread owning kBinsPer consecutive
-// bins.  Returns this thread's first exclusive prefix; h[] its counters, `loc` their total.
-__device__ __forceinline__ int scan_hist(CompressShared& sh, int (&h)[kBinsPer], int& loc) {
+// Scan the kBins counters in sh.hist (each thread owning kBinsPer consecutive bins) and find the
+// bin in which the running count first reaches `need`.  Broadcasts its index, the count in front of
+// it and its own count through sh.piv_*.  Returns nothing; read sh.piv_* after the call.
+__device__ __forceinline__ void find_pivot_bin(CompressShared& sh, int need) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    loc = 0;
+    int h[kBinsPer], loc = 0;
 #pragma unroll
     for (int j = 0; j < kBinsPer; ++j) { h[j] = (int)sh.hist[tid * kBinsPer + j]; loc += h[j]; }
     const int incl = wave_scan_incl(loc);
@@ -93,126 +101,119 @@ __device__ __forceinline__ int scan_hist(CompressShared& sh, int (&h)[kBinsPer],
     int before = 0;
 #pragma unroll
     for (int w = 0; w < kW; ++w) before += (w < wave) ? sh.wtot[w] : 0;
-    return before + incl - loc;
+    const int excl = before + incl - loc;
+    if (excl < need && need <= excl + loc) {   // exactly one thread owns the pivot bin
+        int a = excl, j = 0;
+        while (a + h[j] < need) { a += h[j]; ++j; }
+        sh.piv_bin = tid * kBinsPer + j;
+        sh.piv_before = a;
+        sh.piv_count = h[j];
+    }
+    __syncthreads();
 }
 
-// Composite threshold T with exactly `need` of the n > need candidates >= T.  Every candidate's
-// short key lies in [key_lo, key_hi].
+// What a prune keeps: key > K, or key == K and id <= I.
+struct KeepRule {
+    uint32_t K, I;
+    __device__ __forceinline__ bool keeps(uint32_t key, uint32_t id) const { return key > K || (key == K && id <= I); }
+};
+
+// Exact cut: the rule that keeps exactly `need` of the n > need candidates in LDS, largest keys
+// first, lower ids first among equal keys.  Every candidate's short key lies in [key_lo, key_hi].
+// Radix select on the key, 11 bits per pass below the highest bit of the range; if the pivot key
+// is shared by more candidates than are still needed, a radix select on the id cuts the tie.
 template <bool BF16>
-__device__ __forceinline__ uint64_t select_threshold(CompressShared& sh, int n, int need, uint32_t key_lo, uint32_t key_hi) {
+__device__ __forceinline__ KeepRule select_exact(CompressShared& sh, int n, int need, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x;
-    uint64_t lo = (uint64_t)key_lo << kIdBits;
-    const uint64_t range = (((uint64_t)key_hi << kIdBits) | kIdMask) - lo;
-    const int nb = 64 - __clzll((long long)range);          // range >= kIdMask > 0
+    uint32_t lo = key_lo;
+    const uint32_t range = key_hi - key_lo;
+    const int nb = range ? 32 - __clz((int)range) : 1;
     int shift = nb > kBinsLog2 ? nb - kBinsLog2 : 0;
-    int wbits = 63;   // the window [lo, lo + 2^wbits) holds the candidates still undecided (composites are < 2^52)
+    int wbits = 31;   // undecided candidates have key - lo < 2^(wbits+1); keys below lo wrap far above
+    bool first = true;
     for (;;) {
-#pragma unroll
-        for (int j = 0; j < kBinsPer; ++j) sh.hist[tid + j * kT] = 0;
+        zero_hist(sh);
         __syncthreads();
-#pragma unroll 4
-        for (int j = 0; j < kPer; ++j) {
-            const int i = tid + j * kT;
-            if (i < n) {
-                const uint64_t d = composite<BF16>(make_uint2(sh.cand_val[i], sh.cand_id[i])) - lo;   // below the window wraps to >= 2^63
-                if ((d >> wbits) == 0) atomicAdd(&sh.hist[kBins - 1 - (int)(d >> shift)], 1u);   // reversed: descending
-            }
+        for (int i = tid; i < n; i += kT) {
+            const uint32_t d = short_key<BF16>(sh.cand_val[i]) - lo;
+            if (first || (d >> wbits) == 0) atomicAdd(&sh.hist[kBins - 1 - (int)min(d >> shift, (uint32_t)(kBins - 1))], 1u);   // reversed: descending
         }
         __syncthreads();
-        int h[kBinsPer], loc;
-        const int excl = scan_hist(sh, h, loc);
-        if (excl < need && need <= excl + loc) {   // exactly one thread owns the pivot bin
-            int a = excl, j = 0;
-            while (a + h[j] < need) { a += h[j]; ++j; }
-            sh.piv_rbin = tid * kBinsPer + j;
-            sh.piv_above = a;
-            sh.piv_count = h[j];
-        }
-        __syncthreads();
-        const int bin = kBins - 1 - sh.piv_rbin;
-        need -= sh.piv_above;
+        find_pivot_bin(sh, need);
+        const int bin = kBins - 1 - sh.piv_bin;
+        need -= sh.piv_before;
         const int bcount = sh.piv_count;
-        lo += (uint64_t)bin << shift;
-        if (need == bcount || shift == 0) return lo;   // the whole pivot bin is kept
+        lo += (uint32_t)bin << shift;
+        if (need == bcount) return KeepRule{lo, 0xFFFFFFFFu};   // the whole pivot bin is kept: key >= lo
+        if (shift == 0) break;                                   // lo is the pivot key, shared by bcount > need candidates
+        first = false;
         wbits = shift;
         shift = shift > kBinsLog2 ? shift - kBinsLog2 : 0;
     }
+    // tie on the pivot key: keep the `need` lowest ids among its holders (ids < 2^20: 11 + 9 bits)
+    uint32_t id_lo = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int sh_bits = pass == 0 ? kIdBits - kBinsLog2 : 0;
+        zero_hist(sh);
+        __syncthreads();
+        for (int i = tid; i < n; i += kT) {
+            if (short_key<BF16>(sh.cand_val[i]) == lo) {
+                const uint32_t d = sh.cand_id[i] - id_lo;
+                if (pass == 0 || d < (1u << (kIdBits - kBinsLog2))) atomicAdd(&sh.hist[min(d >> sh_bits, (uint32_t)(kBins - 1))], 1u);
+            }
+        }
+        __syncthreads();
+        find_pivot_bin(sh, need);
+        need -= sh.piv_before;
+        id_lo += (uint32_t)sh.piv_bin << sh_bits;
+        if (pass == 0 && need == sh.piv_count) return KeepRule{lo, id_lo + (1u << sh_bits) - 1u};   // the whole id bin
+    }
+    return KeepRule{lo, id_lo};
 }
 
-// Reduce the n > target candidates to exactly the `target` largest composites, compacted to the
-// front in any order: survivors already in the first `target` slots stay, the others fill the slots
-// vacated there.  With `with_ties` every candidate whose logit equals the target-th one is kept as
-// well (sh.cnt then exceeds target).  Returns the smallest kept logit.
+// Reduce the n > k candidates to exactly the k that `select_exact` keeps, compacted to the front in
+// any order: survivors already in the first k slots stay, the others fill the slots vacated there.
+// Returns a logit not above the smallest kept one (the new admission threshold).
 template <bool BF16>
-__device__ __forceinline__ float prune_to(CompressShared& sh, int n, int target, uint32_t key_lo, uint32_t key_hi,
-                                          bool with_ties) {
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    uint64_t T = select_threshold<BF16>(sh, n, target, key_lo, key_hi);
-    if (with_ties) {   // keep every candidate whose logit equals the target-th one: count them first
-        T = (T >> kIdBits) << kIdBits;
-        int mine = 0;
-#pragma unroll 4
-        for (int j = 0; j < kPer; ++j) {
-            const int i = tid + j * kT;
-            if (i < n) mine += composite<BF16>(make_uint2(sh.cand_val[i], sh.cand_id[i])) >= T ? 1 : 0;
-        }
-        mine = wave_sum(mine);
-        if (lane == 0) sh.wtot[wave] = mine;
-        __syncthreads();
-        target = 0;
-#pragma unroll
-        for (int w = 0; w < kW; ++w) target += sh.wtot[w];
-    }
+__device__ __forceinline__ float prune_to_k(CompressShared& sh, int n, int k, uint32_t key_lo, uint32_t key_hi) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const KeepRule rule = select_exact<BF16>(sh, n, k, key_lo, key_hi);
     uint16_t* holes = reinterpret_cast<uint16_t*>(sh.hist);   // the histogram is free now
     if (tid == 0) { sh.n_holes = 0; sh.n_fills = 0; }
     __syncthreads();
     const unsigned long long below = (1ull << lane) - 1ull;
-    unsigned mk = 0xFFFFFFFFu;
-#pragma unroll 4
-    for (int j = 0; j < kPer; ++j) {   // list the vacated slots; track the smallest kept key
-        const int i = tid + j * kT;
-        bool hole = false;
-        if (i < n) {
-            const uint2 e = make_uint2(sh.cand_val[i], sh.cand_id[i]);
-            const bool kept = composite<BF16>(e) >= T;
-            if (kept) { const unsigned key = key_of_bits(e.x); mk = key < mk ? key : mk; }
-            hole = !kept && i < target;
-        }
+    for (int i0 = 0; i0 < k; i0 += kT) {   // list the vacated slots among the first k
+        const int i = i0 + tid;
+        const bool hole = i < k && !rule.keeps(short_key<BF16>(sh.cand_val[i]), sh.cand_id[i]);
         const unsigned long long hm = __ballot(hole);
         if (hm) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&sh.n_holes, __popcll(hm));
-            base = __shfl(base, 0, kWave);
+            base = __builtin_amdgcn_readfirstlane(base);
             if (hole) holes[base + __popcll(hm & below)] = (uint16_t)i;
         }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { const unsigned w = __shfl_xor(mk, o, kWave); mk = w < mk ? w : mk; }
-    if (lane == 0) sh.wkey[wave] = mk;
     __syncthreads();
-#pragma unroll 4
-    for (int j = 0; j < kPer; ++j) {   // survivors behind `target` move into the vacated slots
-        const int i = tid + j * kT;
+    for (int i0 = k; i0 < n; i0 += kT) {   // survivors behind k move into the vacated slots
+        const int i = i0 + tid;
+        unsigned val = 0, id = 0;
         bool fill = false;
-        uint2 e = make_uint2(0, 0);
-        if (i >= target && i < n) {
-            e = make_uint2(sh.cand_val[i], sh.cand_id[i]);
-            fill = composite<BF16>(e) >= T;
+        if (i < n) {
+            val = sh.cand_val[i];
+            id = sh.cand_id[i];
+            fill = rule.keeps(short_key<BF16>(val), id);
         }
         const unsigned long long fm = __ballot(fill);
         if (fm) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&sh.n_fills, __popcll(fm));
-            base = __shfl(base, 0, kWave);
-            if (fill) { const int h = holes[base + __popcll(fm & below)]; sh.cand_val[h] = e.x; sh.cand_id[h] = e.y; }
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (fill) { const int h = holes[base + __popcll(fm & below)]; sh.cand_val[h] = val; sh.cand_id[h] = id; }
         }
     }
-    unsigned tk = 0xFFFFFFFFu;
-#pragma unroll
-    for (int w = 0; w < kW; ++w) { const unsigned a = sh.wkey[w]; tk = a < tk ? a : tk; }
-    if (tid == 0) sh.cnt = target;
+    if (tid == 0) sh.cnt = k;
     __syncthreads();
-    return __uint_as_float(bits_of_key(tk));
+    return __uint_as_float(bits_of_short_key<BF16>(rule.K));
 }
 
 // Descending bitonic sort of P (power of two) uint64 values in LDS.
@@ -230,22 +231,21 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
     __syncthreads();
 }
 
-// Order the n <= kMaxK candidates at the front of sh.cand by composite, descending; every
+// Order the n <= kMaxK candidates at the front of the buffer by composite, descending; every
 // candidate's short key lies in [key_lo, key_hi].  Returns the LDS array holding the sorted
 // composites.  Histogram rank sort: one pass bins the composites (11 bits below the highest bit of
 // the range), a prefix sum places the bins, and each element's place inside its bin is the number
 // of larger bin-mates.
 template <bool BF16>
 __device__ __forceinline__ const uint64_t* sort_candidates(CompressShared& sh, int n, uint32_t key_lo, uint32_t key_hi) {
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     uint64_t* out = reinterpret_cast<uint64_t*>(sh.cand_val);
     uint64_t* tmp = out + kMaxK;
     const uint64_t lo = (uint64_t)key_lo << kIdBits;
     const uint64_t range = (((uint64_t)key_hi << kIdBits) | kIdMask) - lo;
     const int nb = 64 - __clzll((long long)range);
     const int shift = nb > kBinsLog2 ? nb - kBinsLog2 : 0;
-#pragma unroll
-    for (int j = 0; j < kBinsPer; ++j) sh.hist[tid + j * kT] = 0;
+    zero_hist(sh);
     if (tid == 0) sh.maxbin = 0;
     __syncthreads();
     uint64_t c[kSortPer];
@@ -255,19 +255,23 @@ __device__ __forceinline__ const uint64_t* sort_candidates(CompressShared& sh, i
         const int i = tid + j * kT;
         c[j] = 0; rbin[j] = 0; arrival[j] = 0;
         if (i < n) {
-            c[j] = composite<BF16>(make_uint2(sh.cand_val[i], sh.cand_id[i]));
-            rbin[j] = kBins - 1 - (int)((c[j] - lo) >> shift);
+            c[j] = composite<BF16>(sh.cand_val[i], sh.cand_id[i]);
+            rbin[j] = kBins - 1 - (int)min((c[j] - lo) >> shift, (uint64_t)(kBins - 1));
             arrival[j] = (int)atomicAdd(&sh.hist[rbin[j]], 1u);
         }
     }
     __syncthreads();
-    int h[kBinsPer], loc;
-    int excl = scan_hist(sh, h, loc);
-    int big = 0;
+    // exclusive prefix over the bins, in place; remember the largest bin
+    int h[kBinsPer], loc = 0, big = 0;
 #pragma unroll
-    for (int j = 0; j < kBinsPer; ++j) big = max(big, h[j]);
+    for (int j = 0; j < kBinsPer; ++j) { h[j] = (int)sh.hist[tid * kBinsPer + j]; loc += h[j]; big = max(big, h[j]); }
+    const int incl = wave_scan_incl(loc);
+    if (lane == kWave - 1) sh.wtot[wave] = incl;
     if (big > kSortMaxBin) atomicMax(&sh.maxbin, big);
     __syncthreads();   // every thread has read its counters
+    int excl = incl - loc;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) excl += (w < wave) ? sh.wtot[w] : 0;
 #pragma unroll
     for (int j = 0; j < kBinsPer; ++j) { sh.hist[tid * kBinsPer + j] = (unsigned)excl; excl += h[j]; }
     __syncthreads();
@@ -303,7 +307,7 @@ __device__ __forceinline__ const uint64_t* sort_candidates(CompressShared& sh, i
 }
 
 // Rank r of tile 0 (m elements of a row of V) whose value is expected to have about
-// k + z*sqrt(k) + z^2 row elements at or above it, z = 4.5; 0 if the optimistic mode does not pay.
+// k + z*sqrt(k) + z^2 row elements at or above it, z = 4.5; 0 if the optimistic pass does not pay.
 __device__ __forceinline__ int optimistic_rank(int k, int V, int m) {
     const float r0 = (float)k * (float)m / (float)V;                  // expected rank of the row's k-th value in the tile
     const float r = r0 + 4.5f * sqrtf(r0) + 20.25f;
@@ -321,21 +325,22 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
     extern __shared__ __align__(16) unsigned char smem_raw[];
     CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
     constexpr int N = Vec<BF16>::N, E = NV * N, TILE = kT * E;
-    static_assert(TILE <= kCap, "tile 0 is copied whole into the candidate buffer");
+    static_assert(TILE <= kCap, "tile 0 may be admitted whole");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t row = blockIdx.x;
     const RowView rv = row_view<BF16>(logits, ld, row, V);
     const int n_tiles = (rv.L + TILE - 1) / TILE;
-    const float c = 1.4426950408889634f * inv_T;
-
-    uint4 cur[NV], nxt[NV];
     const int nq = (rv.L + N - 1) / N;           // 16-byte vectors that overlap the row
+    const float c = 1.4426950408889634f * inv_T;
+    const float qnan = __uint_as_float(0x7FC00000u);
+
     auto load_tile = [&](int it, uint4 (&dst)[NV]) {
-        // vectors behind the row's last one re-read that last vector (always a valid address); unpack_tile masks them
+        // vectors behind the row re-read its last vector (always a valid address); unpack_tile masks them
 #pragma unroll
         for (int j = 0; j < NV; ++j) dst[j] = rv.base[min(it * (kT * NV) + j * kT + tid, nq - 1)];
     };
-    // unpack a tile; elements outside the row (alignment prologue, tail) become -inf
+    // Unpack a tile.  Elements outside the row (alignment prologue, tail) become NaN, which fails
+    // every admission test; returns true if the tile has such elements.
     auto unpack_tile = [&](int it, const uint4 (&src)[NV], float (&v)[E]) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
@@ -344,156 +349,213 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
 #pragma unroll
             for (int e = 0; e < N; ++e) v[j * N + e] = t[e];
         }
-        if (it == 0 || it + 1 == n_tiles) {
+        const bool edge = it == 0 || it + 1 == n_tiles;
+        if (edge) {
             unsigned vm = 0;
 #pragma unroll
             for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * (kT * NV) + j * kT + tid) << (j * N);
 #pragma unroll
-            for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : kNegInf;
+            for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : qnan;
         }
+        return edge;
+    };
+    OnlineSum os;
+    // add a tile's elements to the running softmax sum; returns this thread's tile maximum
+    auto tile_stats = [&](const float (&v)[E], bool edge) {
+        float bm = kNegInf;
+#pragma unroll
+        for (int e = 0; e < E; ++e) bm = fmaxf(bm, v[e]);          // fmaxf skips the NaN of masked elements
+        const float mref = os.rebase(bm, c);
+        float acc = 0.f;
+        if (edge) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc += v[e] == v[e] ? exp_stream(v[e], mref, c) : 0.f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc += exp_stream(v[e], mref, c);
+        }
+        os.s += acc;
+        return bm;
+    };
+    // Append the elements of a tile that pass: v > tau, or (ALL) every element that is not NaN.  One
+    // ballot per element column counts the wave's candidates, one LDS atomic reserves their slots, a
+    // second round of ballots places them (the sixteen lane masks are formed twice rather than
+    // kept: they would not fit the scalar file).  Returns the first slot of a reservation that does
+    // not fit (nothing is written then), else -1.
+    auto append_tile = [&](const float (&v)[E], float tau, int x0, auto all_tag) {
+        constexpr bool ALL = decltype(all_tag)::value;
+        int total = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) total += __popcll(__ballot(ALL ? v[e] == v[e] : v[e] > tau));
+        if (total == 0) return -1;
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&sh.cnt, total);
+        base = __builtin_amdgcn_readfirstlane(base);
+        if (base + total > kCap) return base;
+        int run = base;
+        float tau2 = tau;
+        asm volatile("" : "+v"(tau2));
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                const bool pass = ALL ? v[j * N + e] == v[j * N + e] : v[j * N + e] > tau2;
+                const unsigned long long m = __ballot(pass);
+                if (m) {
+                    const int pos = run + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                              __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                    if (pass) {
+                        sh.cand_val[pos] = __float_as_uint(v[j * N + e]);
+                        sh.cand_id[pos] = (unsigned)(x0 + j * kT * N + e);
+                    }
+                    run += __popcll(m);
+                }
+            }
+        return -1;
+    };
+    auto append = [&](const float (&v)[E], float tau, bool all, int x0) {
+        return all ? append_tile(v, tau, x0, std::true_type{}) : append_tile(v, tau, x0, std::false_type{});
     };
 
     const int n0 = min(V, TILE - rv.o);          // row elements in tile 0
     const int r_opt = n_tiles > 1 ? optimistic_rank(k, V, n0) : 0;
-    OnlineSum os;
     float M = kNegInf;
     double S = 0.0;
     uint32_t key_lo = 0, key_hi = 0;
 
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        const bool optimistic = attempt == 0 && r_opt > 0;
+    for (int attempt = r_opt > 0 ? 0 : 1; attempt < 2; ++attempt) {
+        const bool optimistic = attempt == 0;
         if (tid == 0) {
-            sh.cnt = n0;
+            sh.cnt = 0;
+            sh.overflowed = 0;
             for (int e = 0; e < 3; ++e) { sh.epoch_overflow[e] = 0; sh.epoch_valid[e] = 0x7FFFFFFF; }
         }
         os = OnlineSum();
-        int epoch = 0;
+        uint4 cur[NV], nxt[NV];
         load_tile(0, cur);
         if (n_tiles > 1) load_tile(1, nxt);
 
-        // ---- tile 0: statistics, whole tile into the buffer, first cut
-        float tau_adm = kNegInf;                 // later elements are admitted iff > tau_adm
+        // ---- tile 0: statistics and the first threshold
+        float tau = kNegInf;                     // elements are admitted iff > tau ...
+        bool admit_all = true;                   // ... or, before a threshold exists, all of them
         {
             float v[E];
-            unpack_tile(0, cur, v);
-            float bm = v[0], bn = v[0];
+            const bool edge = unpack_tile(0, cur, v);
+            const float bm = tile_stats(v, edge);
+            float bn = __builtin_huge_valf();
 #pragma unroll
-            for (int e = 1; e < E; ++e) { bm = fmaxf(bm, v[e]); bn = fminf(bn, v[e]); }
-            const float mref = os.rebase(bm, c);
-            float acc = 0.f;
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc += exp_stream(v[e], mref, c);
-            os.s += acc;
-#pragma unroll
-            for (int j = 0; j < NV; ++j)
-#pragma unroll
-                for (int e = 0; e < N; ++e) {
-                    const int x = (j * kT + tid) * N + e - rv.o;
-                    if (x >= 0 && x < n0) { sh.cand_val[x] = __float_as_uint(v[j * N + e]); sh.cand_id[x] = (unsigned)x; }
-                }
-            // key range of the tile (masked elements are -inf, which only widens it)
+            for (int e = 0; e < E; ++e) bn = fminf(bn, v[e]);
+            // key range of the tile
             const float wmax = wave_max(bm), wmin = -wave_max(-bn);
             if (lane == 0) { sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax)); sh.wkey[kW + wave] = short_key<BF16>(__float_as_uint(wmin)); }
             __syncthreads();
             key_hi = 0; key_lo = 0xFFFFFFFFu;
 #pragma unroll
             for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); }
+            const int target = optimistic ? r_opt : k;
+            if (n_tiles > 1 && n0 > target && key_hi > key_lo) {
+                // two histogram passes over the keys in registers: a key with >= target elements of the tile at or above it
+                uint32_t lo = key_lo;
+                const uint32_t range = key_hi - key_lo;
+                const int nb = 32 - __clz((int)range);
+                int shift = nb > kBinsLog2 ? nb - kBinsLog2 : 0;
+                int need = target;
+                int wbits = 31;                  // undecided keys have key - lo < 2^(wbits+1) ...
+                for (int pass = 0; pass < 2; ++pass) {
+                    zero_hist(sh);
+                    __syncthreads();
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const uint32_t d = short_key<BF16>(__float_as_uint(v[e])) - lo;   // ... keys below lo wrap far above
+                        if (v[e] == v[e] && (pass == 0 || (d >> wbits) == 0)) atomicAdd(&sh.hist[kBins - 1 - (int)(d >> shift)], 1u);
+                    }
+                    __syncthreads();
+                    find_pivot_bin(sh, need);
+                    need -= sh.piv_before;
+                    lo += (uint32_t)(kBins - 1 - sh.piv_bin) << shift;
+                    if (shift == 0) break;
+                    wbits = shift;
+                    shift = shift > kBinsLog2 ? shift - kBinsLog2 : 0;
+                }
+                const float t = __uint_as_float(bits_of_short_key<BF16>(lo));   // lower edge of the pivot bin
+                if (t > kNegInf) { tau = float_below(t); admit_all = false; key_lo = lo; }
+            }
+            if (admit_all) key_lo = 0;           // later tiles may go below this tile's minimum
             __syncthreads();
-            if (n_tiles > 1) {
-                const int target = optimistic ? r_opt : k;
-                if (n0 > target) {
-                    const float tau = prune_to<BF16>(sh, n0, target, key_lo, key_hi, optimistic);
-                    tau_adm = optimistic ? float_below(tau) : tau;
+            const int failed_at = append(v, tau, admit_all, tid * N - rv.o);
+            if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: a tile fits the empty buffer
+        }
+
+        bool enough = true;
+        if (optimistic) {
+            // ---- tiles 1 .. , optimistic: waves run free; a reservation that does not fit gives the pass up
+            bool fits = true;
+            for (int it = 1; it < n_tiles && fits; ++it) {
+#pragma unroll
+                for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+                if (it + 1 < n_tiles) load_tile(it + 1, nxt);
+                float v[E];
+                const bool edge = unpack_tile(it, cur, v);
+                tile_stats(v, edge);
+                fits = append(v, tau, admit_all, it * TILE - rv.o + tid * N) < 0;
+            }
+            if (!fits && lane == 0) sh.overflowed = 1;
+            __syncthreads();
+            enough = !sh.overflowed && sh.cnt >= k;
+            __syncthreads();                     // everyone has read the verdict before the next attempt resets it
+        } else {
+            // ---- tiles 1 .. , safe: all waves meet after every tile; a full buffer is pruned back to the exact
+            //      top k of everything seen, after which admission is strict
+            int epoch = 0;
+            __syncthreads();
+            for (int it = 1; it < n_tiles; ++it) {
+#pragma unroll
+                for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+                if (it + 1 < n_tiles) load_tile(it + 1, nxt);
+                float v[E];
+                const bool edge = unpack_tile(it, cur, v);
+                tile_stats(v, edge);
+                const int x0 = it * TILE - rv.o + tid * N;
+                bool pending = true;
+                for (;;) {
+                    if (pending) {
+                        const int failed_at = append(v, tau, admit_all, x0);
+                        pending = failed_at >= 0;
+                        if (pending && lane == 0) {
+                            atomicMin(&sh.epoch_valid[epoch], failed_at);
+                            sh.epoch_overflow[epoch] = 1;
+                        }
+                    }
+                    __syncthreads();
+                    const int overflow = sh.epoch_overflow[epoch];
+                    const int n_held = sh.epoch_valid[epoch];
+                    // the slot two epochs ahead was last read before the barrier above and is next
+                    // written after the next barrier
+                    if (tid == 0) { const int e2 = (epoch + 2) % 3; sh.epoch_overflow[e2] = 0; sh.epoch_valid[e2] = 0x7FFFFFFF; }
+                    epoch = (epoch + 1) % 3;
+                    if (!overflow) break;
+                    const float wmax = wave_max(os.m);
+                    if (lane == 0) sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax));
+                    __syncthreads();
+#pragma unroll
+                    for (int w = 0; w < kW; ++w) key_hi = max(key_hi, sh.wkey[w]);
+                    tau = prune_to_k<BF16>(sh, n_held, k, key_lo, key_hi);
+                    admit_all = false;
                     key_lo = short_key<BF16>(__float_as_uint(tau));
                 }
             }
         }
-
-        // ---- tiles 1 .. : admit what beats the threshold
-        bool safe = !optimistic;
-        for (int it = 1; it < n_tiles; ++it) {
-#pragma unroll
-            for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
-            if (it + 1 < n_tiles) load_tile(it + 1, nxt);
-            float v[E];
-            unpack_tile(it, cur, v);
-            float bm = v[0];
-#pragma unroll
-            for (int e = 1; e < E; ++e) bm = fmaxf(bm, v[e]);
-            const float mref = os.rebase(bm, c);
-            float acc = 0.f;
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc += exp_stream(v[e], mref, c);
-            os.s += acc;
-
-            const int x0 = it * TILE - rv.o + tid * N;      // id of this thread's element (j = 0, e = 0)
-            bool pending = true;
-            for (;;) {
-                if (pending) {
-                    // one ballot per element column: which lanes hold a candidate there
-                    int total = 0;
-#pragma unroll
-                    for (int e = 0; e < E; ++e) total += __popcll(__ballot(v[e] > tau_adm));
-                    if (total > 0) {
-                        int base = 0;
-                        if (lane == 0) base = atomicAdd(&sh.cnt, total);
-                        base = __builtin_amdgcn_readfirstlane(base);
-                        if (base + total <= kCap) {
-                            int run = base;
-                            float tau_keep = tau_adm;
-                            asm volatile("" : "+v"(tau_keep));
-#pragma unroll
-                            for (int j = 0; j < NV; ++j)
-#pragma unroll
-                                for (int e = 0; e < N; ++e) {
-                                    // the lane masks are formed again rather than kept: sixteen of them would not fit the scalar file
-                                    const bool pass = v[j * N + e] > tau_keep;
-                                    const unsigned long long m = __ballot(pass);
-                                    const int pos = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
-                                                        __builtin_amdgcn_mbcnt_lo((unsigned)m, (unsigned)run));
-                                    if (pass) {
-                                        sh.cand_val[pos] = __float_as_uint(v[j * N + e]);
-                                        sh.cand_id[pos] = (unsigned)(x0 + j * kT * N + e);
-                                    }
-                                    run += __popcll(m);
-                                }
-                            pending = false;
-                        } else if (lane == 0) {
-                            atomicMin(&sh.epoch_valid[epoch], base);
-                            sh.epoch_overflow[epoch] = 1;
-                        }
-                    } else {
-                        pending = false;
-                    }
-                }
-                __syncthreads();
-                const int overflow = sh.epoch_overflow[epoch];
-                const int n_held = sh.epoch_valid[epoch];
-                // the slot two epochs ahead was last read before the barrier above and is next
-                // written after the next barrier
-                if (tid == 0) { const int e2 = (epoch + 2) % 3; sh.epoch_overflow[e2] = 0; sh.epoch_valid[e2] = 0x7FFFFFFF; }
-                epoch = (epoch + 1) % 3;
-                if (!overflow) break;
-                // the buffer is full: back to the exact top k of everything seen; strict admission from here on
-                const float wmax = wave_max(os.m);
-                if (lane == 0) sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax));
-                __syncthreads();
-#pragma unroll
-                for (int w = 0; w < kW; ++w) key_hi = max(key_hi, sh.wkey[w]);
-                const float tau = prune_to<BF16>(sh, n_held, k, key_lo, key_hi, false);
-                tau_adm = tau;
-                key_lo = short_key<BF16>(__float_as_uint(tau));
-                safe = true;
-            }
-        }
+        if (!enough) continue;                   // optimistic threshold too high, or buffer full: stream again, safely
 
         // ---- end of row
         block_softmax_stats<kW>(os.m, os.s, c, sh.red, M, S);
         key_hi = short_key<BF16>(__float_as_uint(M));
         const int n = sh.cnt;
-        if (n > k) prune_to<BF16>(sh, n, k, key_lo, key_hi, false);
-        if (n >= k || safe) break;               // an optimistic threshold that kept fewer than k: stream again, safely
-        __syncthreads();
+        if (n > k) {
+            const float t = prune_to_k<BF16>(sh, n, k, key_lo, key_hi);
+            key_lo = short_key<BF16>(__float_as_uint(t));
+        }
+        break;
     }
 
     // ---- ordering and emission
@@ -512,9 +574,10 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         int id = -1;
         float pr = 0.f;
         if (slot < n) {
-            const uint2 e = entry_of<BF16>(sorted[slot]);
-            id = (int)e.y;
-            pr = (float)(exp_emit(__uint_as_float(e.x), M, cd) * invS);
+            const uint64_t cv = sorted[slot];
+            id = (int)(kIdMask - ((uint32_t)cv & kIdMask));
+            const float x = __uint_as_float(bits_of_short_key<BF16>((uint32_t)(cv >> kIdBits)));
+            pr = (float)(exp_emit(x, M, cd) * invS);
         }
         bool keep = slot < n;
         if (use_top_p) {   // keep a slot iff the probability before it has not reached top_p
