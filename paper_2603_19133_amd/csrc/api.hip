@@ -103,6 +103,7 @@ int picospec_sample_residual(const void* tgt_logits, int dtype, int64_t ld, int3
     if (B > 0 && (!seq_off || !n_accept || !tgt_max || !tgt_sum || !uniforms || !out_tok || !resid_mass || !flags))
         return PICOSPEC_EINVAL;
     if (n_draft > 0 && (k < 1 || !q_idx || !q_prob || !q_count || !q_mass)) return PICOSPEC_EINVAL;
+    if (n_draft > 0 && k > kMaxK) return PICOSPEC_EUNSUPPORTED;   // records come from picospec_compress
     if (int rc = check_workspace(PICOSPEC_CALL_SAMPLE_RESIDUAL, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
     return hip_status(launch_residual(tgt_logits, dtype, ld, V, temperature, B, seq_off, n_accept, tgt_max, tgt_sum,
                                       q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass,

@@ -68,26 +68,43 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     const int32_t* ids = q_idx + rd * k;
     const float* qp = q_prob + rd * k;
 
-    // residual of the N elements of vector q (tile-relative column j, this lane), given the qhat image
-    auto residual_vec = [&](int it, int jv, int w, int ln, const float* qimg, float (&r)[N]) {
-        const int q = it * (kThreads * NV) + jv * kThreads + w * kWave + ln;
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        const bool in = vec_in_row<BF16>(rv, q);
-        if (in) raw = rv.base[q];
+    // residual of the N elements of the 16-byte vector `raw` = vector q of the row, given the qhat image
+    auto residual_of = [&](const uint4& raw, int q, const float* qimg, float (&r)[N]) {
         float v[N];
         unpack<BF16>(raw, v);
+        const unsigned vm = vec_valid_mask<BF16>(rv, q);
 #pragma unroll
         for (int e = 0; e < N; ++e) {
-            const int x = q * N + e - rv.o;
-            float p = exp_stream(v[e], M, c) * invS;
-            float d = p - qimg[e];
-            r[e] = (in && x >= 0 && x < V && d > 0.f) ? d : 0.f;
+            const float p = exp_stream(v[e], M, c) * invS;
+            const float d = p - qimg[e];
+            r[e] = ((vm >> e) & 1u) && d > 0.f ? d : 0.f;
         }
     };
+    const int nq = (rv.L + N - 1) / N;
+    auto load_vec = [&](int q) { return rv.base[min(q, nq - 1)]; };   // behind the row: its last vector, masked later
+
+    // this thread's share of the sparse record (k <= kMaxK), kept in registers across tiles
+    constexpr int SP = kMaxK / kThreads;
+    int my_id[SP];
+    float my_q[SP];
+#pragma unroll
+    for (int z = 0; z < SP; ++z) {
+        const int s = z * kThreads + tid;
+        my_id[z] = -1;
+        my_q[z] = 0.f;
+        if (s < cnt) { my_id[z] = ids[s]; my_q[z] = qp[s] * q_scale; }
+    }
 
     double R = 0.0;
     for (int attempt = 0; attempt < 2; ++attempt) {
+        uint4 cur[NV], nxt[NV];
+#pragma unroll
+        for (int jv = 0; jv < NV; ++jv) cur[jv] = load_vec(jv * kThreads + tid);
         for (int it = 0; it < n_tiles; ++it) {
+            if (it + 1 < n_tiles) {
+#pragma unroll
+                for (int jv = 0; jv < NV; ++jv) nxt[jv] = load_vec((it + 1) * (kThreads * NV) + jv * kThreads + tid);
+            }
             // qhat image of this tile
             float4* qt4 = reinterpret_cast<float4*>(sh.qtile);
 #pragma unroll
@@ -95,16 +112,17 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
             __syncthreads();
             if (has_q) {
                 const int lo = it * kTile - rv.o;            // id of the tile's first virtual element
-                for (int s = tid; s < cnt; s += kThreads) {
-                    const int off = ids[s] - lo;
-                    if (off >= 0 && off < kTile) sh.qtile[off] = qp[s] * q_scale;
+#pragma unroll
+                for (int z = 0; z < SP; ++z) {
+                    const int off = my_id[z] - lo;
+                    if (my_id[z] >= 0 && off >= 0 && off < kTile) sh.qtile[off] = my_q[z];
                 }
             }
             __syncthreads();
 #pragma unroll
             for (int jv = 0; jv < NV; ++jv) {
                 float r[N];
-                residual_vec(it, jv, wave, lane, sh.qtile + (jv * kThreads + tid) * N, r);
+                residual_of(cur[jv], it * (kThreads * NV) + jv * kThreads + tid, sh.qtile + (jv * kThreads + tid) * N, r);
                 double sum = 0.0;
 #pragma unroll
                 for (int e = 0; e < N; ++e) sum += (double)r[e];
@@ -112,6 +130,8 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
                 if (lane == 0) sh.seg[(it * NV + jv) * kWaves + wave] = sum;
             }
             __syncthreads();
+#pragma unroll
+            for (int jv = 0; jv < NV; ++jv) cur[jv] = nxt[jv];
         }
         // total residual mass
         double part = 0.0;
@@ -167,15 +187,18 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         for (int e = 0; e < N; ++e) sh.qtile[lane * N + e] = 0.f;
     }
     __syncthreads();
-    if (wave == 0 && has_q)
-        for (int s = lane; s < cnt; s += kWave) {
-            const int off = ids[s] - seg_lo;
-            if (off >= 0 && off < kWave * N) sh.qtile[off] = qp[s] * q_scale;
+    if (has_q) {
+#pragma unroll
+        for (int z = 0; z < SP; ++z) {
+            const int off = my_id[z] - seg_lo;
+            if (my_id[z] >= 0 && off >= 0 && off < kWave * N) sh.qtile[off] = my_q[z];
         }
+    }
     __syncthreads();
     if (wave == 0) {
         float r[N];
-        residual_vec(it, jv, pw, lane, sh.qtile + lane * N, r);
+        const int qv = it * (kThreads * NV) + jv * kThreads + pw * kWave + lane;
+        residual_of(load_vec(qv), qv, sh.qtile + lane * N, r);
         double sum = 0.0;
 #pragma unroll
         for (int e = 0; e < N; ++e) sum += (double)r[e];

@@ -44,14 +44,11 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
             for (int e = 0; e < N; ++e) v[j * N + e] = t[e];
         }
         if (it == 0 || it == n_tiles - 1) {
-            const int x0 = it * TILE - rv.o;
+            unsigned vm = 0;
 #pragma unroll
-            for (int j = 0; j < NV; ++j)
+            for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * (kThreads * NV) + j * kThreads + tid) << (j * N);
 #pragma unroll
-                for (int e = 0; e < N; ++e) {
-                    int x = x0 + (j * kThreads + tid) * N + e;
-                    if (x < 0 || x >= V) v[j * N + e] = kNegInf;
-                }
+            for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : kNegInf;
         }
         float bm = v[0];
 #pragma unroll
@@ -73,9 +70,10 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
     }
 }
 
-// One workgroup (4 waves) per sequence, one wave per draft position.
+// One workgroup (16 waves) per sequence, one wave per draft position.  The wave looks the drafted
+// token up in the position's sparse record with 16-byte loads (four in flight per lane).
 template <bool BF16>
-__global__ __launch_bounds__(256) void accept_kernel(
+__global__ __launch_bounds__(kThreads) void accept_kernel(
     const void* __restrict__ tgt_logits, int64_t ld, int V, float inv_T, int B,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ draft_tok,
     const int32_t* __restrict__ q_idx, const float* __restrict__ q_prob,
@@ -87,7 +85,7 @@ __global__ __launch_bounds__(256) void accept_kernel(
 {
     __shared__ int s_first;
     __shared__ unsigned s_flags;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, n_waves = blockDim.x / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int b = blockIdx.x;
     const int d0 = seq_off[b];
     int g = seq_off[b + 1] - d0;
@@ -99,12 +97,12 @@ __global__ __launch_bounds__(256) void accept_kernel(
     const double cd = 1.4426950408889634 * (double)inv_T;
 
     // every target row of the sequence must have finite statistics
-    for (int t = tid; t <= g; t += blockDim.x) {
+    for (int t = tid; t <= g; t += kThreads) {
         float M = tgt_max[t0 + t], S = tgt_sum[t0 + t];
         if (!(fabsf(M) < __builtin_huge_valf()) || !(S > 0.f) || !(S < __builtin_huge_valf())) fl |= 2u;
     }
 
-    for (int i = wave; i < g; i += n_waves) {
+    for (int i = wave; i < g; i += kWaves) {
         const int64_t rd = (int64_t)d0 + i, rt = t0 + i;
         const int x = draft_tok[rd];
         const bool bad = x < 0 || x >= V;
@@ -116,8 +114,24 @@ __global__ __launch_bounds__(256) void accept_kernel(
             cnt = cnt < 0 ? 0 : (cnt > k ? k : cnt);
             const int32_t* ids = q_idx + rd * k;
             int slot = -1;
-            for (int s = lane; s < cnt; s += kWave)
-                if (ids[s] == x) slot = s;
+            if ((((uintptr_t)ids) & 15u) == 0) {
+                const int4* ids4 = reinterpret_cast<const int4*>(ids);
+                const int n4 = cnt >> 2;
+#pragma unroll 4
+                for (int s = lane; s < n4; s += kWave) {
+                    const int4 q = ids4[s];
+                    if (q.x == x) slot = 4 * s;
+                    if (q.y == x) slot = 4 * s + 1;
+                    if (q.z == x) slot = 4 * s + 2;
+                    if (q.w == x) slot = 4 * s + 3;
+                }
+                for (int s = 4 * n4 + lane; s < cnt; s += kWave)
+                    if (ids[s] == x) slot = s;
+            } else {
+#pragma unroll 8
+                for (int s = lane; s < cnt; s += kWave)
+                    if (ids[s] == x) slot = s;
+            }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) slot = max(slot, __shfl_xor(slot, o, kWave));
             if (slot >= 0 && !bad) {
@@ -171,8 +185,8 @@ hipError_t launch_accept(const void* tgt_logits, int dtype, int64_t ld, int V, f
 {
     if (B == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
-    if (dtype == 1) hipLaunchKernelGGL(accept_kernel<true>, dim3(B), dim3(256), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
-    else            hipLaunchKernelGGL(accept_kernel<false>, dim3(B), dim3(256), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
+    if (dtype == 1) hipLaunchKernelGGL(accept_kernel<true>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
+    else            hipLaunchKernelGGL(accept_kernel<false>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
     return hipGetLastError();
 }
 
