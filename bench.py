@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (debugging)")
     ap.add_argument("--cpu-seqs", type=int, default=-1, help="sequences in the oracle's timed sample (0 = skip)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -96,6 +98,13 @@ def main() -> int:
         if ev:
             ev[3].record()
 
+    if args.copy_probe_mib:
+        src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -137,7 +146,7 @@ def main() -> int:
     }
 
     # the CPU oracle, as it stands, on a bounded sample of the same workload
-    n_cpu = args.cpu_seqs if args.cpu_seqs >= 0 else max(1, min(B, 16 if w.V > 100000 else 64))
+    n_cpu = args.cpu_seqs if args.cpu_seqs >= 0 else min(B, 128)
     if n_cpu > 0:
         import oracle
         sub = W.build_round(w, 0, seqs=range(n_cpu))

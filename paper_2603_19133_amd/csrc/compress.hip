@@ -394,7 +394,8 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         if (base + total > kCap) return base;
         int run = base;
         float tau2 = tau;
-        asm volatile("" : "+v"(tau2));
+        int xb = x0;
+        asm volatile("" : "+v"(tau2), "+v"(xb));   // also keeps the sixteen ids from being formed ahead of time
 #pragma unroll
         for (int j = 0; j < NV; ++j)
 #pragma unroll
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
                                               __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
                     if (pass) {
                         sh.cand_val[pos] = __float_as_uint(v[j * N + e]);
-                        sh.cand_id[pos] = (unsigned)(x0 + j * kT * N + e);
+                        sh.cand_id[pos] = (unsigned)(xb + j * kT * N + e);
                     }
                     run += __popcll(m);
                 }
