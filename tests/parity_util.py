@@ -156,3 +156,25 @@ def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: fl
     assert st["mismatch_draw"] <= max(1, int(max_excluded_frac * B)), st
     st["accept_rate"] = float(o.ver.n_accept.sum() / max(1, r.N))
     return st
+
+
+def slice_gpu_round(g: GpuRound, full: W.Round, sub: W.Round) -> GpuRound:
+    """The outputs of the sequences of `sub` (a subset of `full`'s sequences, same round) cut out of a
+    full-batch GPU result and re-packed in `sub`'s layout, so that compare_round applies unchanged."""
+    pos = {int(b): j for j, b in enumerate(full.seqs)}
+    d_rows, t_rows, seq_ix = [], [], []
+    for b in sub.seqs:
+        j = pos[int(b)]
+        d0, d1 = int(full.seq_off[j]), int(full.seq_off[j + 1])
+        d_rows += list(range(d0, d1))
+        t_rows += list(range(d0 + j, d1 + j + 1))
+        seq_ix.append(j)
+    d = torch.tensor(d_rows, dtype=torch.long)
+    t = torch.tensor(t_rows, dtype=torch.long)
+    s = torch.tensor(seq_ix, dtype=torch.long)
+    c = lambda x, ix: x.detach().cpu()[ix]
+    q = ps.Compressed(c(g.q.idx, d), c(g.q.prob, d), c(g.q.count, d), c(g.q.mass, d), c(g.q.lse, d), g.q.k)
+    ver = ps.Verified(c(g.ver.n_accept, s), c(g.ver.p_tok, d), c(g.ver.q_tok, d), c(g.ver.tgt_max, t),
+                      c(g.ver.tgt_sum, t), c(g.ver.tgt_lse, t), c(g.ver.flags, s))
+    res = ps.Residual(c(g.res.out_tok, s), c(g.res.resid_mass, s), c(g.res.flags, s))
+    return GpuRound(q, ver, res)

@@ -296,3 +296,57 @@ def test_empty_batch(gpu, ps):
     res = ps.sample_residual(tgt, 64, 1.0, seq_off, 0, ver, q, z)
     torch.cuda.synchronize()
     assert ver.n_accept.numel() == 0 and res.out_tok.numel() == 0
+
+
+# ---------------------------------------------------------------- full-size rounds, sampled sequences
+
+FULL_CASES = [("cfg3", 0, 8), ("cfg4", 0, 6), ("cfg5", 0, 6), ("cfg5", 1, 4), ("cfg5", 50, 4), ("cfg5", 99, 6)]
+
+
+@pytest.mark.parametrize("name,rnd,n_sample", FULL_CASES)
+def test_full_size_round_sampled_sequences(gpu, pu, ps, name, rnd, n_sample):
+    """The whole batch at its real size goes through the library exactly as bench.py launches it (same calls,
+    same shapes); a seeded sample of sequences is checked element by element against the oracle, which
+    regenerates just those sequences.  Everything else is checked through size-independent properties."""
+    w = W.WORKLOADS[name]
+    _announce("full size", name, "round", rnd, "B", w.B, "V", w.V, "k", w.k, w.dtype)
+    full = W.build_round(w, rnd)
+    pick = np.sort(np.random.default_rng(1000 + rnd).choice(w.B, size=n_sample, replace=False))
+    sub = W.build_round(w, rnd, seqs=pick)
+    o = pu.oracle_round(sub)
+    dev = lambda a: pu.to_device(a, gpu)
+    draft, tgt = dev(full.draft_logits), dev(full.tgt_logits)
+    seq_off, uni = dev(full.seq_off), dev(full.uniforms)
+    q = ps.compress(draft, w.V, w.T, w.k, w.top_p)
+    tok, _ = ps.sample_draft(q, dev(full.draft_uniforms))
+    # the sampled sequences get the oracle's drafted tokens, so both sides verify the same draft
+    tok_h = pu.n(tok).copy()
+    for j, b in enumerate(pick):
+        tok_h[full.seq_off[b]:full.seq_off[b + 1]] = o.tok[sub.seq_off[j]:sub.seq_off[j + 1]]
+    tok = dev(tok_h)
+    ver = ps.verify(tgt, w.V, w.T, seq_off, full.N, tok, q, uni)
+    res = ps.sample_residual(tgt, w.V, w.T, seq_off, full.N, ver, q, uni)
+    torch.cuda.synchronize()
+    g = pu.GpuRound(q, ver, res)
+    st = pu.compare_round(pu.slice_gpu_round(g, full, sub), o, sub, max_excluded_frac=0.2)
+    print("[stats]", name, rnd, {k: v for k, v in st.items() if k != "topp_excluded"}, flush=True)
+    # properties that hold for every row and sequence of the batch
+    idx, prob, cnt, mass = pu.n(q.idx), pu.n(q.prob), pu.n(q.count), pu.n(q.mass)
+    assert ((cnt >= 1) & (cnt <= w.k)).all()
+    used = np.arange(w.k)[None, :] < cnt[:, None]
+    assert (idx[used] >= 0).all() and (idx[used] < w.V).all() and (idx[~used] == -1).all() and (prob[~used] == 0).all()
+    assert (np.diff(prob, axis=1)[used[:, 1:]] <= 0).all()                      # descending probabilities
+    srt = np.sort(np.where(used, idx, np.arange(w.k)[None, :] + w.V), axis=1)   # ids are distinct within a row
+    assert (np.diff(srt, axis=1) > 0).all()
+    assert np.allclose(np.where(used, prob, 0).sum(1), mass, rtol=1e-5) and (mass <= 1 + 1e-5).all()
+    if w.top_p <= 0:
+        assert (cnt == w.k).all()
+    g_len = np.diff(full.seq_off)
+    na = pu.n(ver.n_accept)
+    assert ((na >= 0) & (na <= g_len)).all()
+    out = pu.n(res.out_tok)
+    assert ((out >= 0) & (out < w.V)).all()
+    rm = pu.n(res.resid_mass)
+    assert ((rm > 0) & (rm <= 1 + 1e-5)).all()
+    assert np.allclose(rm[na == g_len], 1.0, rtol=1e-5)                          # bonus draws come from P itself
+    assert (pu.n(ver.flags) == 0).all() and (pu.n(res.flags) == 0).all()
