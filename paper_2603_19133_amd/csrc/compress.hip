@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
     auto load_tile = [&](int it, uint4 (&dst)[NV]) {
         // vectors behind the row re-read its last vector (always a valid address); unpack_tile masks them
 #pragma unroll
-        for (int j = 0; j < NV; ++j) dst[j] = rv.base[min(it * (kT * NV) + j * kT + tid, nq - 1)];
+        for (int j = 0; j < NV; ++j) dst[j] = load16_stream(rv.base + min(it * (kT * NV) + j * kT + tid, nq - 1));
     };
     // Unpack a tile.  Elements outside the row (alignment prologue, tail) become NaN, which fails
     // every admission test; returns true if the tile has such elements.

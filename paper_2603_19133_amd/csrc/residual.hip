@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         }
     };
     const int nq = (rv.L + N - 1) / N;
-    auto load_vec = [&](int q) { return rv.base[min(q, nq - 1)]; };   // behind the row: its last vector, masked later
+    auto load_vec = [&](int q) { return load16_stream(rv.base + min(q, nq - 1)); };   // behind the row: its last vector, masked later
 
     // this thread's share of the sparse record (k <= kMaxK), kept in registers across tiles
     constexpr int SP = kMaxK / kThreads;

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
         for (int j = 0; j < NV; ++j) {
             int q = it * (kThreads * NV) + j * kThreads + tid;
             dst[j] = make_uint4(0, 0, 0, 0);
-            if (vec_in_row<BF16>(rv, q)) dst[j] = rv.base[q];
+            if (vec_in_row<BF16>(rv, q)) dst[j] = load16_stream(rv.base + q);
         }
     };
     load_tile(0, cur);
