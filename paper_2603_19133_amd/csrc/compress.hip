@@ -2,9 +2,11 @@
 // softmax statistics: one workgroup of 512 threads per row, two workgroups per CU, one HBM pass
 // per row.
 //
-// Streaming selection.  A row is read in tiles of 16-byte vectors (8192 elements per tile).
-//   * Tile 0 stays in registers while a two-pass radix histogram over its order-preserving logit
-//     keys finds a threshold: a value with at least r of the tile's elements at or above it.
+// Streaming selection.  A row is read in sub-tiles of two 16-byte vectors per thread through a ring
+// of four register buffers (three sub-tiles in flight behind the one being processed).
+//   * The first 8192 elements (the sample) stay in registers while a two-pass radix histogram over
+//     their order-preserving logit keys finds a threshold: a value with at least r of the sample's
+//     elements at or above it.
 //   * Optimistic pass: r is chosen so that about k + 4.5 sqrt(k) + 20 elements of the whole row are
 //     expected at or above the threshold (for exchangeable rows).  Every element of the row at
 //     or above it -- tile 0 included -- is appended to a candidate buffer in LDS (value, id).
@@ -316,7 +318,7 @@ __device__ __forceinline__ int optimistic_rank(int k, int V, int m) {
     return (int)ceilf(r);
 }
 
-template <bool BF16, int NV>
+template <bool BF16>
 __global__ __launch_bounds__(kT, 4) void compress_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
@@ -324,69 +326,76 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
-    constexpr int N = Vec<BF16>::N, E = NV * N, TILE = kT * E;
-    static_assert(TILE <= kCap, "tile 0 may be admitted whole");
+    // A row is streamed in sub-tiles of SV 16-byte vectors per thread.  The first T0 sub-tiles (8192
+    // elements) form the sample from which the threshold is taken; they are processed together.
+    constexpr int N = Vec<BF16>::N;
+    constexpr int SV = 2, ES = SV * N, SUB = kT * ES;       // 4096 (fp32) / 8192 (bf16) elements per sub-tile
+    constexpr int SAMPLE = 8192, T0 = SAMPLE / SUB, NV0 = T0 * SV, E0 = NV0 * N;
+    constexpr int RING = 4;                                  // sub-tile buffers: one in use, three in flight
+    static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t row = blockIdx.x;
     const RowView rv = row_view<BF16>(logits, ld, row, V);
-    const int n_tiles = (rv.L + TILE - 1) / TILE;
+    const int n_sub = (rv.L + SUB - 1) / SUB;
     const int nq = (rv.L + N - 1) / N;           // 16-byte vectors that overlap the row
     const float c = 1.4426950408889634f * inv_T;
     const float qnan = __uint_as_float(0x7FC00000u);
 
-    auto load_tile = [&](int it, uint4 (&dst)[NV]) {
-        // vectors behind the row re-read its last vector (always a valid address); unpack_tile masks them
+    auto load_sub = [&](int sub, uint4 (&dst)[SV]) {
+        // vectors behind the row re-read its last vector (always a valid address); unpack masks them
 #pragma unroll
-        for (int j = 0; j < NV; ++j) dst[j] = load16_stream(rv.base + min(it * (kT * NV) + j * kT + tid, nq - 1));
+        for (int j = 0; j < SV; ++j) dst[j] = load16_stream(rv.base + min(sub * (kT * SV) + j * kT + tid, nq - 1));
     };
-    // Unpack a tile.  Elements outside the row (alignment prologue, tail) become NaN, which fails
-    // every admission test; returns true if the tile has such elements.
-    auto unpack_tile = [&](int it, const uint4 (&src)[NV], float (&v)[E]) {
+    // Unpack NVV vectors, vector jj being vector q0 + jj*kT of the row.  With `edge`, elements outside
+    // the row (alignment prologue, tail) become NaN, which fails every admission test.
+    auto unpack_vecs = [&](auto nvv_tag, int q0, const uint4* src, float* v, bool edge) {
+        constexpr int NVV = decltype(nvv_tag)::value;
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
+        for (int j = 0; j < NVV; ++j) {
             float t[N];
             unpack<BF16>(src[j], t);
 #pragma unroll
             for (int e = 0; e < N; ++e) v[j * N + e] = t[e];
         }
-        const bool edge = it == 0 || it + 1 == n_tiles;
         if (edge) {
             unsigned vm = 0;
 #pragma unroll
-            for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * (kT * NV) + j * kT + tid) << (j * N);
+            for (int j = 0; j < NVV; ++j) vm |= vec_valid_mask<BF16>(rv, q0 + j * kT) << (j * N);
 #pragma unroll
-            for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : qnan;
+            for (int e = 0; e < NVV * N; ++e) v[e] = (vm >> e) & 1u ? v[e] : qnan;
         }
-        return edge;
     };
     OnlineSum os;
-    // add a tile's elements to the running softmax sum; returns this thread's tile maximum
-    auto tile_stats = [&](const float (&v)[E], bool edge) {
+    // add EE elements to the running softmax sum; returns this thread's maximum over them
+    auto add_stats = [&](auto ee_tag, const float* v, bool edge) {
+        constexpr int EE = decltype(ee_tag)::value;
         float bm = kNegInf;
 #pragma unroll
-        for (int e = 0; e < E; ++e) bm = fmaxf(bm, v[e]);          // fmaxf skips the NaN of masked elements
+        for (int e = 0; e < EE; ++e) bm = fmaxf(bm, v[e]);          // fmaxf skips the NaN of masked elements
         const float mref = os.rebase(bm, c);
         float acc = 0.f;
         if (edge) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc += v[e] == v[e] ? exp_stream(v[e], mref, c) : 0.f;
+            for (int e = 0; e < EE; ++e) acc += v[e] == v[e] ? exp_stream(v[e], mref, c) : 0.f;
         } else {
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc += exp_stream(v[e], mref, c);
+            for (int e = 0; e < EE; ++e) acc += exp_stream(v[e], mref, c);
         }
         os.s += acc;
         return bm;
     };
-    // Append the elements of a tile that pass: v > tau, or (ALL) every element that is not NaN.  One
-    // ballot per element column counts the wave's candidates, one LDS atomic reserves their slots, a
-    // second round of ballots places them (the sixteen lane masks are formed twice rather than
-    // kept: they would not fit the scalar file).  Returns the first slot of a reservation that does
-    // not fit (nothing is written then), else -1.
-    auto append_tile = [&](const float (&v)[E], float tau, int x0, auto all_tag) {
+    // Append the elements that pass: v > tau, or (ALL) every element that is not NaN.  One ballot per
+    // element column counts the wave's candidates, one LDS atomic reserves their slots, a second
+    // round of ballots places them (the lane masks are formed twice rather than kept: sixteen of
+    // them would not fit the scalar file).  x0 = id of this thread's first element; vector jj starts
+    // kT*N ids after vector jj-1.  Returns the first slot of a reservation that does not fit
+    // (nothing is written then), else -1.
+    auto append_vecs = [&](auto nvv_tag, auto all_tag, const float* v, float tau, int x0) {
+        constexpr int NVV = decltype(nvv_tag)::value;
         constexpr bool ALL = decltype(all_tag)::value;
         int total = 0;
 #pragma unroll
-        for (int e = 0; e < E; ++e) total += __popcll(__ballot(ALL ? v[e] == v[e] : v[e] > tau));
+        for (int e = 0; e < NVV * N; ++e) total += __popcll(__ballot(ALL ? v[e] == v[e] : v[e] > tau));
         if (total == 0) return -1;
         int base = 0;
         if (lane == 0) base = atomicAdd(&sh.cnt, total);
@@ -395,9 +404,9 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         int run = base;
         float tau2 = tau;
         int xb = x0;
-        asm volatile("" : "+v"(tau2), "+v"(xb));   // also keeps the sixteen ids from being formed ahead of time
+        asm volatile("" : "+v"(tau2), "+v"(xb));   // also keeps the ids from being formed ahead of time
 #pragma unroll
-        for (int j = 0; j < NV; ++j)
+        for (int j = 0; j < NVV; ++j)
 #pragma unroll
             for (int e = 0; e < N; ++e) {
                 const bool pass = ALL ? v[j * N + e] == v[j * N + e] : v[j * N + e] > tau2;
@@ -414,12 +423,17 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
             }
         return -1;
     };
-    auto append = [&](const float (&v)[E], float tau, bool all, int x0) {
-        return all ? append_tile(v, tau, x0, std::true_type{}) : append_tile(v, tau, x0, std::false_type{});
+    auto append = [&](auto nvv_tag, const float* v, float tau, bool all, int x0) {
+        return all ? append_vecs(nvv_tag, std::true_type{}, v, tau, x0) : append_vecs(nvv_tag, std::false_type{}, v, tau, x0);
     };
+    using sv_t = std::integral_constant<int, SV>;
+    using es_t = std::integral_constant<int, ES>;
+    using nv0_t = std::integral_constant<int, NV0>;
+    using e0_t = std::integral_constant<int, E0>;
 
-    const int n0 = min(V, TILE - rv.o);          // row elements in tile 0
-    const int r_opt = n_tiles > 1 ? optimistic_rank(k, V, n0) : 0;
+    const bool more = n_sub > T0;                // the row goes on behind the sample
+    const int n0 = min(V, SAMPLE - rv.o);        // row elements in the sample
+    const int r_opt = more ? optimistic_rank(k, V, n0) : 0;
     float M = kNegInf;
     double S = 0.0;
     uint32_t key_lo = 0, key_hi = 0;
@@ -432,21 +446,21 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
             for (int e = 0; e < 3; ++e) { sh.epoch_overflow[e] = 0; sh.epoch_valid[e] = 0x7FFFFFFF; }
         }
         os = OnlineSum();
-        uint4 cur[NV], nxt[NV];
-        load_tile(0, cur);
-        if (n_tiles > 1) load_tile(1, nxt);
+        uint4 rb[RING][SV];
+#pragma unroll
+        for (int t = 0; t < RING; ++t) load_sub(t, rb[t]);
 
-        // ---- tile 0: statistics and the first threshold
+        // ---- the sample: statistics and the first threshold
         float tau = kNegInf;                     // elements are admitted iff > tau ...
         bool admit_all = true;                   // ... or, before a threshold exists, all of them
         {
-            float v[E];
-            const bool edge = unpack_tile(0, cur, v);
-            const float bm = tile_stats(v, edge);
+            float v[E0];
+            unpack_vecs(nv0_t{}, tid, &rb[0][0], v, true);
+            const float bm = add_stats(e0_t{}, v, true);
             float bn = __builtin_huge_valf();
 #pragma unroll
-            for (int e = 0; e < E; ++e) bn = fminf(bn, v[e]);
-            // key range of the tile
+            for (int e = 0; e < E0; ++e) bn = fminf(bn, v[e]);
+            // key range of the sample
             const float wmax = wave_max(bm), wmin = -wave_max(-bn);
             if (lane == 0) { sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax)); sh.wkey[kW + wave] = short_key<BF16>(__float_as_uint(wmin)); }
             __syncthreads();
@@ -454,8 +468,8 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
 #pragma unroll
             for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); }
             const int target = optimistic ? r_opt : k;
-            if (n_tiles > 1 && n0 > target && key_hi > key_lo) {
-                // two histogram passes over the keys in registers: a key with >= target elements of the tile at or above it
+            if (more && n0 > target && key_hi > key_lo) {
+                // two histogram passes over the keys in registers: a key with >= target elements of the sample at or above it
                 uint32_t lo = key_lo;
                 const uint32_t range = key_hi - key_lo;
                 const int nb = 32 - __clz((int)range);
@@ -466,7 +480,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
                     zero_hist(sh);
                     __syncthreads();
 #pragma unroll
-                    for (int e = 0; e < E; ++e) {
+                    for (int e = 0; e < E0; ++e) {
                         const uint32_t d = short_key<BF16>(__float_as_uint(v[e])) - lo;   // ... keys below lo wrap far above
                         if (v[e] == v[e] && (pass == 0 || (d >> wbits) == 0)) atomicAdd(&sh.hist[kBins - 1 - (int)(d >> shift)], 1u);
                     }
@@ -481,46 +495,57 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
                 const float t = __uint_as_float(bits_of_short_key<BF16>(lo));   // lower edge of the pivot bin
                 if (t > kNegInf) { tau = float_below(t); admit_all = false; key_lo = lo; }
             }
-            if (admit_all) key_lo = 0;           // later tiles may go below this tile's minimum
+            if (admit_all) key_lo = 0;           // later sub-tiles may go below the sample's minimum
             __syncthreads();
-            const int failed_at = append(v, tau, admit_all, tid * N - rv.o);
-            if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: a tile fits the empty buffer
+            const int failed_at = append(nv0_t{}, v, tau, admit_all, tid * N - rv.o);
+            if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: the sample fits the empty buffer
         }
 
         bool enough = true;
         if (optimistic) {
-            // ---- tiles 1 .. , optimistic: waves run free; a reservation that does not fit gives the pass up
-            bool fits = true;
-            for (int it = 1; it < n_tiles && fits; ++it) {
+            // ---- behind the sample, optimistic: waves run free; a reservation that does not fit gives the
+            //      pass up.  The ring buffers rotate by role (no copies): while one sub-tile is processed
+            //      three are in flight; loads behind the row are clamped, so they need no guard.
 #pragma unroll
-                for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
-                if (it + 1 < n_tiles) load_tile(it + 1, nxt);
-                float v[E];
-                const bool edge = unpack_tile(it, cur, v);
-                tile_stats(v, edge);
-                fits = append(v, tau, admit_all, it * TILE - rv.o + tid * N) < 0;
+            for (int t = 0; t < T0; ++t) load_sub(RING + t, rb[t]);
+            bool fits = true;
+            auto step = [&](int sub, uint4 (&buf)[SV]) {
+                if (sub < n_sub && fits) {
+                    float v[ES];
+                    const bool edge = sub + 1 == n_sub;
+                    unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, edge);
+                    add_stats(es_t{}, v, edge);
+                    fits = append(sv_t{}, v, tau, admit_all, sub * SUB - rv.o + tid * N) < 0;
+                }
+                load_sub(sub + RING, buf);
+            };
+            for (int sub = T0; sub < n_sub; sub += RING) {
+                step(sub, rb[T0 % RING]);
+                step(sub + 1, rb[(T0 + 1) % RING]);
+                step(sub + 2, rb[(T0 + 2) % RING]);
+                step(sub + 3, rb[(T0 + 3) % RING]);
             }
             if (!fits && lane == 0) sh.overflowed = 1;
             __syncthreads();
             enough = !sh.overflowed && sh.cnt >= k;
             __syncthreads();                     // everyone has read the verdict before the next attempt resets it
         } else {
-            // ---- tiles 1 .. , safe: all waves meet after every tile; a full buffer is pruned back to the exact
-            //      top k of everything seen, after which admission is strict
+            // ---- behind the sample, safe: all waves meet after every sub-tile; a full buffer is pruned back to
+            //      the exact top k of everything seen, after which admission is strict.  (Rare path: no prefetch.)
             int epoch = 0;
             __syncthreads();
-            for (int it = 1; it < n_tiles; ++it) {
-#pragma unroll
-                for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
-                if (it + 1 < n_tiles) load_tile(it + 1, nxt);
-                float v[E];
-                const bool edge = unpack_tile(it, cur, v);
-                tile_stats(v, edge);
-                const int x0 = it * TILE - rv.o + tid * N;
+            for (int sub = T0; sub < n_sub; ++sub) {
+                uint4 cur[SV];
+                load_sub(sub, cur);
+                float v[ES];
+                const bool edge = sub + 1 == n_sub;
+                unpack_vecs(sv_t{}, sub * (kT * SV) + tid, cur, v, edge);
+                add_stats(es_t{}, v, edge);
+                const int x0 = sub * SUB - rv.o + tid * N;
                 bool pending = true;
                 for (;;) {
                     if (pending) {
-                        const int failed_at = append(v, tau, admit_all, x0);
+                        const int failed_at = append(sv_t{}, v, tau, admit_all, x0);
                         pending = failed_at >= 0;
                         if (pending && lane == 0) {
                             atomicMin(&sh.epoch_valid[epoch], failed_at);
@@ -662,8 +687,8 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
 {
     static bool attr_set[2] = {false, false};
     const size_t smem = sizeof(CompressShared);
-    auto f32 = compress_kernel<false, 4>;
-    auto b16 = compress_kernel<true, 2>;
+    auto f32 = compress_kernel<false>;
+    auto b16 = compress_kernel<true>;
     const int which = dtype == 1;
     if (!attr_set[which]) {
         hipError_t e = hipFuncSetAttribute(which ? (const void*)b16 : (const void*)f32,
