@@ -384,23 +384,29 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         os.s += acc;
         return bm;
     };
-    // Append the elements that pass: v > tau, or (ALL) every element that is not NaN.  One ballot per
-    // element column counts the wave's candidates, one LDS atomic reserves their slots, a second
-    // round of ballots places them (the lane masks are formed twice rather than kept: sixteen of
-    // them would not fit the scalar file).  x0 = id of this thread's first element; vector jj starts
-    // kT*N ids after vector jj-1.  Returns the first slot of a reservation that does not fit
-    // (nothing is written then), else -1.
-    auto append_vecs = [&](auto nvv_tag, auto all_tag, const float* v, float tau, int x0) {
+    // Appending the elements that pass (v > tau, or with ALL every element that is not NaN) takes two
+    // steps so that independent work can sit between them and hide the LDS atomic's latency:
+    // reserve_vecs counts the wave's candidates (one ballot per element column) and reserves their
+    // slots with one LDS atomic; place_vecs forms the lane masks again (sixteen of them would not fit
+    // the scalar file) and writes (value, id).  x0 = id of this thread's first element; vector jj
+    // starts kT*N ids after vector jj-1.
+    struct Reservation { int total, base; };   // base is valid in lane 0 until place_vecs broadcasts it
+    auto reserve_vecs = [&](auto nvv_tag, auto all_tag, const float* v, float tau) {
         constexpr int NVV = decltype(nvv_tag)::value;
         constexpr bool ALL = decltype(all_tag)::value;
-        int total = 0;
+        Reservation r{0, 0};
 #pragma unroll
-        for (int e = 0; e < NVV * N; ++e) total += __popcll(__ballot(ALL ? v[e] == v[e] : v[e] > tau));
-        if (total == 0) return -1;
-        int base = 0;
-        if (lane == 0) base = atomicAdd(&sh.cnt, total);
-        base = __builtin_amdgcn_readfirstlane(base);
-        if (base + total > kCap) return base;
+        for (int e = 0; e < NVV * N; ++e) r.total += __popcll(__ballot(ALL ? v[e] == v[e] : v[e] > tau));
+        if (r.total > 0 && lane == 0) r.base = atomicAdd(&sh.cnt, r.total);
+        return r;
+    };
+    // Returns the first slot of a reservation that does not fit (nothing is written then), else -1.
+    auto place_vecs = [&](auto nvv_tag, auto all_tag, const float* v, float tau, int x0, Reservation r) {
+        constexpr int NVV = decltype(nvv_tag)::value;
+        constexpr bool ALL = decltype(all_tag)::value;
+        if (r.total == 0) return -1;
+        const int base = __builtin_amdgcn_readfirstlane(r.base);
+        if (base + r.total > kCap) return base;
         int run = base;
         float tau2 = tau;
         int xb = x0;
@@ -424,7 +430,8 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         return -1;
     };
     auto append = [&](auto nvv_tag, const float* v, float tau, bool all, int x0) {
-        return all ? append_vecs(nvv_tag, std::true_type{}, v, tau, x0) : append_vecs(nvv_tag, std::false_type{}, v, tau, x0);
+        if (all) return place_vecs(nvv_tag, std::true_type{}, v, tau, x0, reserve_vecs(nvv_tag, std::true_type{}, v, tau));
+        return place_vecs(nvv_tag, std::false_type{}, v, tau, x0, reserve_vecs(nvv_tag, std::false_type{}, v, tau));
     };
     using sv_t = std::integral_constant<int, SV>;
     using es_t = std::integral_constant<int, ES>;
@@ -514,8 +521,15 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
                     float v[ES];
                     const bool edge = sub + 1 == n_sub;
                     unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, edge);
-                    add_stats(es_t{}, v, edge);
-                    fits = append(sv_t{}, v, tau, admit_all, sub * SUB - rv.o + tid * N) < 0;
+                    const int x0 = sub * SUB - rv.o + tid * N;
+                    if (admit_all) {             // only until the sample yields a threshold (rows of -inf)
+                        add_stats(es_t{}, v, edge);
+                        fits = append(sv_t{}, v, tau, true, x0) < 0;
+                    } else {                     // the statistics sit between reservation and placement
+                        const Reservation r = reserve_vecs(sv_t{}, std::false_type{}, v, tau);
+                        add_stats(es_t{}, v, edge);
+                        fits = place_vecs(sv_t{}, std::false_type{}, v, tau, x0, r) < 0;
+                    }
                 }
                 load_sub(sub + RING, buf);
             };
