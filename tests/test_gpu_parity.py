@@ -350,3 +350,20 @@ def test_full_size_round_sampled_sequences(gpu, pu, ps, name, rnd, n_sample):
     assert ((rm > 0) & (rm <= 1 + 1e-5)).all()
     assert np.allclose(rm[na == g_len], 1.0, rtol=1e-5)                          # bonus draws come from P itself
     assert (pu.n(ver.flags) == 0).all() and (pu.n(res.flags) == 0).all()
+
+
+def test_acceptance_is_strict_at_the_boundary(gpu, pu, ps):
+    """u == p/q rejects, one ulp below accepts (V = 1: p = 1 exactly; scalar q = 2: ratio = 1/2 exactly)."""
+    _announce("strict boundary")
+    dev = lambda a: pu.to_device(a, gpu)
+    tgt = np.zeros((6, 1), np.float32)
+    off = np.array([0, 1, 2, 3], np.int32)
+    tok = np.zeros(3, np.int32)
+    below = np.nextafter(np.float32(0.5), np.float32(0.0))
+    uni = np.array([0.5, 0.0, below, 0.0, np.nextafter(np.float32(0.5), np.float32(1.0)), 0.0], np.float32)
+    qs = np.array([2.0, 2.0, 2.0], np.float32)
+    o = oracle.verify(tgt, 1, 1.0, off, tok, None, uni, q_scalar=qs.astype(np.float64))
+    v = ps.verify(dev(tgt), 1, 1.0, dev(off), 3, dev(tok), None, dev(uni), q_scalar=dev(qs))
+    torch.cuda.synchronize()
+    assert list(pu.n(v.n_accept)) == list(o.n_accept) == [0, 1, 0]
+    assert list(pu.n(v.p_tok)) == [1.0, 1.0, 1.0]

@@ -428,3 +428,16 @@ def test_sample_draft_is_inverse_cdf_over_slots():
     _, sl, _ = oracle.sample_draft(qq, rng.random(100_000, dtype=np.float32))
     exp = qq.prob[0] / qq.mass[0] * 100_000
     assert scipy.stats.chisquare(np.bincount(sl, minlength=9), exp).pvalue > 1e-3
+
+
+def test_acceptance_is_strict_at_the_boundary():
+    """u < min(1, p/q) with equality rejected: V = 1 makes p = 1 exactly, the scalar q makes p/q = 1/2 exactly."""
+    tgt = np.zeros((6, 1), np.float32)                       # three sequences, gamma = 1 each
+    off = np.array([0, 1, 2, 3], np.int32)
+    tok = np.zeros(3, np.int32)
+    below = np.nextafter(np.float32(0.5), np.float32(0.0))
+    uni = np.array([0.5, 0.0, below, 0.0, np.nextafter(np.float32(0.5), np.float32(1.0)), 0.0], np.float32)
+    v = oracle.verify(tgt, 1, 1.0, off, tok, None, uni, q_scalar=np.array([2.0, 2.0, 2.0]))
+    assert list(v.p_tok) == [1.0, 1.0, 1.0]
+    assert list(v.n_accept) == [0, 1, 0]                     # u == ratio rejects, one ulp below accepts
+    assert v.margin[0] == 0.0
