@@ -18,10 +18,12 @@
 //     every tile; when the buffer is full it is pruned to the exact top k of everything seen, and
 //     from then on an element must be strictly larger than the k-th (rows are streamed in
 //     ascending id, so equal logits that come later lose the tie).
-//   * The survivors are cut to exactly k by a radix select on the key, ties at the k-th key cut by
-//     a radix select on the id (lower id wins), ordered by a histogram rank sort on the composite
+//   * The candidates are cut to exactly k and ordered in one step by a histogram rank sort on the
+//     composite
 //         (key << 20) | (2^20 - 1 - id)
-//     their probabilities formed from the row's (max, sum), and the record written once.
+//     (larger logit first, lower id first among equal logits), their probabilities formed from the
+//     row's (max, sum), and the record written once.  The cut of a mid-row prune is a radix select
+//     on the key, ties at the k-th key cut by a radix select on the id.
 #include <type_traits>
 
 #include "common.hpp"
@@ -39,10 +41,12 @@ constexpr int kBins = 1 << kBinsLog2;       // histogram bins of the radix selec
 constexpr int kBinsPer = kBins / kT;
 constexpr int kIdBits = 20;                 // ids < 2^20 (kMaxV)
 constexpr unsigned kIdMask = (1u << kIdBits) - 1u;
-constexpr int kSortMaxBin = 48;             // rank sort falls back to a bitonic network beyond this bin size
+constexpr int kSortMaxBin = 128;            // beyond this bin size the ordering falls back to a sorting network
 constexpr int kSortPer = kMaxK / kT;
+constexpr int kCandPer = kCap / kT;
 
-static_assert(kMaxK * 2 <= kCap, "the rank sort uses two k-sized regions of the candidate buffer");
+static_assert(kMaxK <= kCap && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
+static_assert(kCap < 65536 && kBins <= 32768, "bin and arrival order of a candidate share one register");
 static_assert(kMaxV <= (1 << kIdBits), "id field of the composite key");
 static_assert(kCap <= 65536 && kCap / 2 * 2 <= kBins * 4, "a prune keeps a 16-bit index list in the histogram");
 
@@ -233,79 +237,103 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
     __syncthreads();
 }
 
-// Order the n <= kMaxK candidates at the front of the buffer by composite, descending; every
-// candidate's short key lies in [key_lo, key_hi].  Returns the LDS array holding the sorted
-// composites.  Histogram rank sort: one pass bins the composites (11 bits below the highest bit of
-// the range), a prefix sum places the bins, and each element's place inside its bin is the number
-// of larger bin-mates.
+// Cut the n <= kCap candidates in the buffer to the min(n, k) largest by composite and order them,
+// descending; every candidate's short key lies in [key_lo, key_hi].  Returns the LDS array that
+// holds the ordered composites.  One histogram pass does both jobs: the candidates (held in
+// registers from here on) are binned by their place in the (key, id) order, scaled linearly so that
+// the kBins bins cover [key_lo, key_hi] x [0, V) evenly (rows with few distinct logits spread over
+// the bins by id); a prefix sum over the bins, largest first, finds the bin in which the k-th
+// largest falls; the candidates of the bins up to that one are gathered bin by bin, each one's
+// place inside its bin is the number of larger bin-mates, and the places below k are kept.
+// A bin too crowded for that (one outlier stretching the key range) sends the row through the
+// radix select and a sorting network instead.
 template <bool BF16>
-__device__ __forceinline__ const uint64_t* sort_candidates(CompressShared& sh, int n, uint32_t key_lo, uint32_t key_hi) {
+__device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    uint64_t* out = reinterpret_cast<uint64_t*>(sh.cand_val);
-    uint64_t* tmp = out + kMaxK;
-    const uint64_t lo = (uint64_t)key_lo << kIdBits;
-    const uint64_t range = (((uint64_t)key_hi << kIdBits) | kIdMask) - lo;
-    const int nb = 64 - __clzll((long long)range);
-    const int shift = nb > kBinsLog2 ? nb - kBinsLog2 : 0;
+    uint64_t* buf = reinterpret_cast<uint64_t*>(sh.cand_val);   // cand_val and cand_id, back to back
+    const double dV = (double)V;
+    const double scale = (double)kBins / (((double)(key_hi - key_lo) + 1.0) * dV);
     zero_hist(sh);
-    if (tid == 0) sh.maxbin = 0;
+    if (tid == 0) { sh.maxbin = 0; sh.piv_bin = kBins - 1; sh.piv_before = n; }
     __syncthreads();
-    uint64_t c[kSortPer];
-    int rbin[kSortPer], arrival[kSortPer];
+    uint64_t c[kCandPer];
+    int meta[kCandPer];                      // (bin << 16) | arrival order within the bin; -1: no candidate
 #pragma unroll
-    for (int j = 0; j < kSortPer; ++j) {
+    for (int j = 0; j < kCandPer; ++j) {
         const int i = tid + j * kT;
-        c[j] = 0; rbin[j] = 0; arrival[j] = 0;
+        c[j] = 0; meta[j] = -1;
         if (i < n) {
-            c[j] = composite<BF16>(sh.cand_val[i], sh.cand_id[i]);
-            rbin[j] = kBins - 1 - (int)min((c[j] - lo) >> shift, (uint64_t)(kBins - 1));
-            arrival[j] = (int)atomicAdd(&sh.hist[rbin[j]], 1u);
+            const uint32_t bits = sh.cand_val[i], id = sh.cand_id[i];
+            c[j] = composite<BF16>(bits, id);
+            const double place = (double)(short_key<BF16>(bits) - key_lo) * dV + (double)(V - 1 - (int)id);
+            const int rbin = kBins - 1 - min((int)(place * scale), kBins - 1);   // reversed: bin 0 holds the largest
+            meta[j] = (rbin << 16) | (int)atomicAdd(&sh.hist[rbin], 1u);
         }
     }
     __syncthreads();
-    // exclusive prefix over the bins, in place; remember the largest bin
-    int h[kBinsPer], loc = 0, big = 0;
+    // exclusive prefix over the bins, in place; the bin that holds the k-th largest; the most crowded bin in front of it
+    int h[kBinsPer], loc = 0;
 #pragma unroll
-    for (int j = 0; j < kBinsPer; ++j) { h[j] = (int)sh.hist[tid * kBinsPer + j]; loc += h[j]; big = max(big, h[j]); }
+    for (int j = 0; j < kBinsPer; ++j) { h[j] = (int)sh.hist[tid * kBinsPer + j]; loc += h[j]; }
     const int incl = wave_scan_incl(loc);
     if (lane == kWave - 1) sh.wtot[wave] = incl;
-    if (big > kSortMaxBin) atomicMax(&sh.maxbin, big);
     __syncthreads();   // every thread has read its counters
     int excl = incl - loc;
 #pragma unroll
     for (int w = 0; w < kW; ++w) excl += (w < wave) ? sh.wtot[w] : 0;
+    int big = 0;
 #pragma unroll
-    for (int j = 0; j < kBinsPer; ++j) { sh.hist[tid * kBinsPer + j] = (unsigned)excl; excl += h[j]; }
+    for (int j = 0; j < kBinsPer; ++j) {
+        sh.hist[tid * kBinsPer + j] = (unsigned)excl;
+        if (excl < k) {
+            big = max(big, h[j]);
+            if (excl + h[j] >= k) { sh.piv_bin = tid * kBinsPer + j; sh.piv_before = excl + h[j]; }
+        }
+        excl += h[j];
+    }
+    if (big > kSortMaxBin) atomicMax(&sh.maxbin, big);
     __syncthreads();
-    if (sh.maxbin > kSortMaxBin) {   // degenerate spread (e.g. one outlier stretching the range): plain network
+    if (sh.maxbin > kSortMaxBin) {
+        __syncthreads();                     // (prune_to_k writes the words read above)
+        if (n > k) { prune_to_k<BF16>(sh, n, k, key_lo, key_hi); n = k; }
+        // the survivors' composites go to registers, then into the buffer padded to a power of two
+#pragma unroll
+        for (int j = 0; j < kSortPer; ++j) {
+            const int i = tid + j * kT;
+            c[j] = i < n ? composite<BF16>(sh.cand_val[i], sh.cand_id[i]) : 0;
+        }
         int P = 1;
         while (P < n) P <<= 1;
-        for (int i = tid; i < P; i += kT) tmp[i] = 0;
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < kSortPer; ++j) { const int i = tid + j * kT; if (i < n) tmp[i] = c[j]; }
-        bitonic_sort_desc(tmp, P);
-        return tmp;
+        for (int j = 0; j < kSortPer; ++j) { const int i = tid + j * kT; if (i < P) buf[i] = c[j]; }
+        bitonic_sort_desc(buf, P);
+        return buf;
     }
+    const int piv = sh.piv_bin, n_keep = sh.piv_before;
+    // gather bin by bin (every candidate is in registers: the buffer may be overwritten)
 #pragma unroll
-    for (int j = 0; j < kSortPer; ++j) {
-        const int i = tid + j * kT;
-        if (i < n) tmp[(int)sh.hist[rbin[j]] + arrival[j]] = c[j];
-    }
-    __syncthreads();   // all candidates are in registers and in tmp: their old slots may be overwritten
+    for (int j = 0; j < kCandPer; ++j)
+        if (meta[j] >= 0 && (meta[j] >> 16) <= piv) buf[(int)sh.hist[meta[j] >> 16] + (meta[j] & 0xFFFF)] = c[j];
+    __syncthreads();
+    int pos[kCandPer];
 #pragma unroll
-    for (int j = 0; j < kSortPer; ++j) {
-        const int i = tid + j * kT;
-        if (i < n) {
-            const int s = (int)sh.hist[rbin[j]];
-            const int e = rbin[j] + 1 < kBins ? (int)sh.hist[rbin[j] + 1] : n;
+    for (int j = 0; j < kCandPer; ++j) {
+        pos[j] = k;
+        if (meta[j] >= 0 && (meta[j] >> 16) <= piv) {
+            const int rbin = meta[j] >> 16;
+            const int s = (int)sh.hist[rbin];
+            const int e = rbin < piv ? (int)sh.hist[rbin + 1] : n_keep;
             int larger = 0;
-            for (int q = s; q < e; ++q) larger += tmp[q] > c[j] ? 1 : 0;
-            out[s + larger] = c[j];
+            for (int q = s; q < e; ++q) larger += buf[q] > c[j] ? 1 : 0;
+            pos[j] = s + larger;
         }
     }
+    __syncthreads();                         // all places are known before the ordered list overwrites the bins
+#pragma unroll
+    for (int j = 0; j < kCandPer; ++j) if (pos[j] < k) buf[pos[j]] = c[j];
     __syncthreads();
-    return out;
+    return buf;
 }
 
 // Rank r of tile 0 (m elements of a row of V) whose value is expected to have about
@@ -502,7 +530,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
                 const float t = __uint_as_float(bits_of_short_key<BF16>(lo));   // lower edge of the pivot bin
                 if (t > kNegInf) { tau = float_below(t); admit_all = false; key_lo = lo; }
             }
-            if (admit_all) key_lo = 0;           // later sub-tiles may go below the sample's minimum
+            if (admit_all && more) key_lo = 0;   // later sub-tiles may go below the sample's minimum
             __syncthreads();
             const int failed_at = append(nv0_t{}, v, tau, admit_all, tid * N - rv.o);
             if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: the sample fits the empty buffer
@@ -590,17 +618,13 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         // ---- end of row
         block_softmax_stats<kW>(os.m, os.s, c, sh.red, M, S);
         key_hi = short_key<BF16>(__float_as_uint(M));
-        const int n = sh.cnt;
-        if (n > k) {
-            const float t = prune_to_k<BF16>(sh, n, k, key_lo, key_hi);
-            key_lo = short_key<BF16>(__float_as_uint(t));
-        }
         break;
     }
 
-    // ---- ordering and emission
-    const int n = min(sh.cnt, k);
-    const uint64_t* sorted = sort_candidates<BF16>(sh, n, key_lo, key_hi);
+    // ---- exact cut to k, ordering and emission
+    const int n_held = sh.cnt;
+    const int n = min(n_held, k);
+    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi);
 
     const double cd = 1.4426950408889634 * (double)inv_T;
     const double invS = 1.0 / S;
