@@ -10,9 +10,12 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpicospec.so")
 SOURCES = ["api.hip", "compress.hip", "verify.hip", "residual.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed-fp32 instructions are switched off (scalar fp32 code only)
+# packed-fp32 instructions are switched off (scalar fp32 code only); the compiler's rewrite of
+# same-address LDS atomics into a wave-wide scan is switched off (the compress kernel issues one
+# atomic per passing element on purpose: a few lanes each, no vector ALU work)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:

@@ -91,6 +91,13 @@ __device__ __forceinline__ double exp_emit(float x, float m, double c) {
     return ldexp((double)exp2f(f), (int)n);
 }
 
+// 2^a for a double exponent of any magnitude (split into integer and fraction as in exp_emit).
+__device__ __forceinline__ double exp2_split(double a) {
+    if (!(a > -1100.0)) return 0.0;
+    double n = rint(a);
+    return ldexp((double)exp2f((float)(a - n)), (int)n);
+}
+
 // ---------------------------------------------------------------- row streaming
 //
 // A row of V elements is read as 16-byte vectors.  If the row does not start on a 16-byte

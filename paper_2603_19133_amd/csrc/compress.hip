@@ -33,7 +33,10 @@ namespace picospec {
 
 namespace {
 
-constexpr int kT = 512;                     // threads per workgroup (8 waves)
+#ifndef PICOSPEC_COMPRESS_THREADS
+#define PICOSPEC_COMPRESS_THREADS 512
+#endif
+constexpr int kT = PICOSPEC_COMPRESS_THREADS;   // threads per workgroup
 constexpr int kW = kT / kWave;
 constexpr int kCap = 8192;                  // candidate slots in LDS (value + id, 8 bytes)
 constexpr int kBinsLog2 = 11;
@@ -46,6 +49,7 @@ constexpr int kSortPer = kMaxK / kT;
 constexpr int kCandPer = kCap / kT;
 
 static_assert(kMaxK <= kCap && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
+static_assert((kCap & (kCap - 1)) == 0, "slots wrap around the buffer by masking");
 static_assert(kCap < 65536 && kBins <= 32768, "bin and arrival order of a candidate share one register");
 static_assert(kMaxV <= (1 << kIdBits), "id field of the composite key");
 static_assert(kCap <= 65536 && kCap / 2 * 2 <= kBins * 4, "a prune keeps a 16-bit index list in the histogram");
@@ -347,7 +351,7 @@ __device__ __forceinline__ int optimistic_rank(int k, int V, int m) {
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(kT, 4) void compress_kernel(
+__global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
     float* __restrict__ mass, float* __restrict__ lse)
@@ -357,9 +361,13 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
     // A row is streamed in sub-tiles of SV 16-byte vectors per thread.  The first T0 sub-tiles (8192
     // elements) form the sample from which the threshold is taken; they are processed together.
     constexpr int N = Vec<BF16>::N;
-    constexpr int SV = 2, ES = SV * N, SUB = kT * ES;       // 4096 (fp32) / 8192 (bf16) elements per sub-tile
-    constexpr int SAMPLE = 8192, T0 = SAMPLE / SUB, NV0 = T0 * SV, E0 = NV0 * N;
-    constexpr int RING = 4;                                  // sub-tile buffers: one in use, three in flight
+    constexpr int SAMPLE = 8192;
+    constexpr int SV = (2 * kT * N <= SAMPLE) ? 2 : 1, ES = SV * N, SUB = kT * ES;
+    constexpr int T0 = SAMPLE / SUB, NV0 = T0 * SV, E0 = NV0 * N;
+#ifndef PICOSPEC_COMPRESS_RING
+#define PICOSPEC_COMPRESS_RING 4
+#endif
+    constexpr int RING = PICOSPEC_COMPRESS_RING * (2 / SV);  // sub-tile buffers: one in use, the others in flight
     static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t row = blockIdx.x;
@@ -393,21 +401,29 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
             for (int e = 0; e < NVV * N; ++e) v[e] = (vm >> e) & 1u ? v[e] : qnan;
         }
     };
-    OnlineSum os;
-    // add EE elements to the running softmax sum; returns this thread's maximum over them
+    // Running softmax sum of this thread: s = sum 2^(v*c - r) with an integer reference exponent
+    // r >= c * (largest value seen), so that one fused multiply-add forms each exponent (and a change
+    // of reference scales s by an exact power of two); mx = largest value seen.
+    struct { float mx, r, s; } os;
+    // add EE elements to the running sum; returns this thread's maximum over them
     auto add_stats = [&](auto ee_tag, const float* v, bool edge) {
         constexpr int EE = decltype(ee_tag)::value;
         float bm = kNegInf;
 #pragma unroll
         for (int e = 0; e < EE; ++e) bm = fmaxf(bm, v[e]);          // fmaxf skips the NaN of masked elements
-        const float mref = os.rebase(bm, c);
+        if (bm > os.mx) {
+            os.mx = bm;
+            const float rn = ceilf(bm * c);
+            if (rn > os.r) { os.s *= __builtin_amdgcn_exp2f(os.r - rn); os.r = rn; }   // r = -inf: s is 0 and stays 0
+        }
+        const float nr = os.r == kNegInf ? 0.f : -os.r;             // rows of only -inf so far
         float acc = 0.f;
         if (edge) {
 #pragma unroll
-            for (int e = 0; e < EE; ++e) acc += v[e] == v[e] ? exp_stream(v[e], mref, c) : 0.f;
+            for (int e = 0; e < EE; ++e) acc += v[e] == v[e] ? __builtin_amdgcn_exp2f(fmaf(v[e], c, nr)) : 0.f;
         } else {
 #pragma unroll
-            for (int e = 0; e < EE; ++e) acc += exp_stream(v[e], mref, c);
+            for (int e = 0; e < EE; ++e) acc += __builtin_amdgcn_exp2f(fmaf(v[e], c, nr));
         }
         os.s += acc;
         return bm;
@@ -480,7 +496,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
             sh.overflowed = 0;
             for (int e = 0; e < 3; ++e) { sh.epoch_overflow[e] = 0; sh.epoch_valid[e] = 0x7FFFFFFF; }
         }
-        os = OnlineSum();
+        os.mx = kNegInf; os.r = kNegInf; os.s = 0.f;
         uint4 rb[RING][SV];
 #pragma unroll
         for (int t = 0; t < RING; ++t) load_sub(t, rb[t]);
@@ -541,35 +557,65 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
             // ---- behind the sample, optimistic: waves run free; a reservation that does not fit gives the
             //      pass up.  The ring buffers rotate by role (no copies): while one sub-tile is processed
             //      three are in flight; loads behind the row are clamped, so they need no guard.
+            const bool applies = !admit_all;     // a sample without a threshold (rows of -inf) leaves the row to the safe pass
+            if (applies) {
 #pragma unroll
-            for (int t = 0; t < T0; ++t) load_sub(RING + t, rb[t]);
-            bool fits = true;
-            auto step = [&](int sub, uint4 (&buf)[SV]) {
-                if (sub < n_sub && fits) {
+                for (int t = 0; t < T0; ++t) load_sub(RING + t, rb[t]);
+                // Every element above the threshold claims a slot with an LDS atomic of its own (a few lanes
+                // per instruction); the statistics sit between the claims and the writes that need the
+                // slots.  A claim at or behind the end of the buffer writes nothing: the count tells.
+                typedef __attribute__((address_space(3))) int lds_int;
+                lds_int* cnt_lds = (lds_int*)&sh.cnt;
+                asm volatile("" : "+v"(cnt_lds));                   // the counter's address stays in one register
+                auto claim = [&](const float* v, int* slot) {
+#pragma unroll
+                    for (int e = 0; e < ES; ++e)
+                        if (v[e] > tau) slot[e] = __hip_atomic_fetch_add(cnt_lds, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                };
+                // Slots wrap around the buffer: once the count has passed its end the pass is lost anyway.
+                auto put = [&](const float* v, const int* slot, int x0) {
+#pragma unroll
+                    for (int j = 0; j < SV; ++j)
+#pragma unroll
+                        for (int e = 0; e < N; ++e)
+                            if (v[j * N + e] > tau) {
+                                int at = slot[j * N + e];
+                                asm volatile("" : "+v"(at));        // the mask stays here, behind the statistics
+                                at &= kCap - 1;
+                                sh.cand_val[at] = __float_as_uint(v[j * N + e]);
+                                sh.cand_id[at] = (unsigned)(x0 + j * kT * N + e);
+                            }
+                };
+                auto full = [&](int sub, uint4 (&buf)[SV]) {        // a sub-tile wholly inside the row
                     float v[ES];
-                    const bool edge = sub + 1 == n_sub;
-                    unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, edge);
-                    const int x0 = sub * SUB - rv.o + tid * N;
-                    if (admit_all) {             // only until the sample yields a threshold (rows of -inf)
-                        add_stats(es_t{}, v, edge);
-                        fits = append(sv_t{}, v, tau, true, x0) < 0;
-                    } else {                     // the statistics sit between reservation and placement
-                        const Reservation r = reserve_vecs(sv_t{}, std::false_type{}, v, tau);
-                        add_stats(es_t{}, v, edge);
-                        fits = place_vecs(sv_t{}, std::false_type{}, v, tau, x0, r) < 0;
+                    int slot[ES];
+                    unpack_vecs(sv_t{}, 0, buf, v, false);
+                    claim(v, slot);
+                    add_stats(es_t{}, v, false);
+                    put(v, slot, sub * SUB - rv.o + tid * N);
+                    load_sub(sub + RING, buf);
+                };
+                auto ragged = [&](int sub, uint4 (&buf)[SV]) {      // any sub-tile: what lies behind the row is masked
+                    if (sub < n_sub) {
+                        float v[ES];
+                        int slot[ES];
+                        unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, true);
+                        claim(v, slot);
+                        add_stats(es_t{}, v, true);
+                        put(v, slot, sub * SUB - rv.o + tid * N);
                     }
+                };
+                // the hot loop holds nothing but the common case, RING times (one copy per buffer role)
+                int sub = T0;
+                for (; sub + RING < n_sub; sub += RING) {
+#pragma unroll
+                    for (int r = 0; r < RING; ++r) full(sub + r, rb[(T0 + r) % RING]);
                 }
-                load_sub(sub + RING, buf);
-            };
-            for (int sub = T0; sub < n_sub; sub += RING) {
-                step(sub, rb[T0 % RING]);
-                step(sub + 1, rb[(T0 + 1) % RING]);
-                step(sub + 2, rb[(T0 + 2) % RING]);
-                step(sub + 3, rb[(T0 + 3) % RING]);
+#pragma unroll
+                for (int r = 0; r < RING; ++r) ragged(sub + r, rb[(T0 + r) % RING]);
             }
-            if (!fits && lane == 0) sh.overflowed = 1;
             __syncthreads();
-            enough = !sh.overflowed && sh.cnt >= k;
+            enough = applies && !sh.overflowed && sh.cnt >= k && sh.cnt <= kCap;
             __syncthreads();                     // everyone has read the verdict before the next attempt resets it
         } else {
             // ---- behind the sample, safe: all waves meet after every sub-tile; a full buffer is pruned back to
@@ -602,7 +648,7 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
                     if (tid == 0) { const int e2 = (epoch + 2) % 3; sh.epoch_overflow[e2] = 0; sh.epoch_valid[e2] = 0x7FFFFFFF; }
                     epoch = (epoch + 1) % 3;
                     if (!overflow) break;
-                    const float wmax = wave_max(os.m);
+                    const float wmax = wave_max(os.mx);
                     if (lane == 0) sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax));
                     __syncthreads();
 #pragma unroll
@@ -616,7 +662,22 @@ __global__ __launch_bounds__(kT, 4) void compress_kernel(
         if (!enough) continue;                   // optimistic threshold too high, or buffer full: stream again, safely
 
         // ---- end of row
-        block_softmax_stats<kW>(os.m, os.s, c, sh.red, M, S);
+        {   // M = max over the threads; S = sum s * 2^(r - M*c), combined in fp64
+            const float wm = wave_max(os.mx);
+            if (lane == 0) sh.red[wave] = (double)wm;
+            __syncthreads();
+            M = kNegInf;
+#pragma unroll
+            for (int w = 0; w < kW; ++w) M = fmaxf(M, (float)sh.red[w]);
+            const double mine = os.r == kNegInf ? 0.0 : (double)os.s * exp2_split((double)os.r - (double)M * (double)c);
+            const double ws = wave_sum(mine);
+            if (lane == 0) sh.red[kW + wave] = ws;
+            __syncthreads();
+            S = 0.0;
+#pragma unroll
+            for (int w = 0; w < kW; ++w) S += sh.red[kW + w];
+            __syncthreads();
+        }
         key_hi = short_key<BF16>(__float_as_uint(M));
         break;
     }
