@@ -47,6 +47,8 @@ constexpr unsigned kIdMask = (1u << kIdBits) - 1u;
 constexpr int kSortMaxBin = 128;            // beyond this bin size the ordering falls back to a sorting network
 constexpr int kSortPer = kMaxK / kT;
 constexpr int kCandPer = kCap / kT;
+constexpr int kCoarseLog2 = 8;
+constexpr int kCoarse = 1 << kCoarseLog2;   // coarse ranges that steer the fine bins of the rank sort
 
 static_assert(kMaxK <= kCap && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
 static_assert((kCap & (kCap - 1)) == 0, "slots wrap around the buffer by masking");
@@ -58,6 +60,7 @@ struct __align__(16) CompressShared {
     unsigned cand_val[kCap];                // candidates: fp32 bit pattern ...
     unsigned cand_id[kCap];                 // ... and vocabulary id (the sort reuses both arrays as uint64 regions)
     unsigned hist[kBins];
+    unsigned coarse[kCoarse];               // rank sort: count, then (fine bins << 16) | first fine bin, per coarse range
     double red[2 * kW];
     int wtot[kW];
     unsigned wkey[2 * kW];
@@ -243,35 +246,75 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
 
 // Cut the n <= kCap candidates in the buffer to the min(n, k) largest by composite and order them,
 // descending; every candidate's short key lies in [key_lo, key_hi].  Returns the LDS array that
-// holds the ordered composites.  One histogram pass does both jobs: the candidates (held in
-// registers from here on) are binned by their place in the (key, id) order, scaled linearly so that
-// the kBins bins cover [key_lo, key_hi] x [0, V) evenly (rows with few distinct logits spread over
-// the bins by id); a prefix sum over the bins, largest first, finds the bin in which the k-th
-// largest falls; the candidates of the bins up to that one are gathered bin by bin, each one's
-// place inside its bin is the number of larger bin-mates, and the places below k are kept.
-// A bin too crowded for that (one outlier stretching the key range) sends the row through the
-// radix select and a sorting network instead.
+// holds the ordered composites.  A histogram rank sort does both jobs, on candidates held in
+// registers from here on.
+//   * A candidate's place p = ((key_hi - key) << ib) | (leading ib bits of its id) is a 32-bit
+//     integer that never decreases along the wanted order (larger logit first, lower id first);
+//     ib is as many id bits as fit next to the key range (all of them for rows with few distinct
+//     logits, so that equal logits spread over the bins by id).
+//   * A coarse histogram of p (kCoarse equal ranges) measures where the candidates lie; each
+//     coarse range then gets a share of the kBins fine bins in proportion to its count, so that
+//     fine bins hold a few candidates each whatever the distribution of the logits.
+//   * A prefix sum over the fine bins finds the bin in which the k-th largest falls; the
+//     candidates of the bins up to that one are gathered bin by bin, each one's position inside
+//     its bin is the number of larger bin-mates, and the positions below k are kept.
+// A bin too crowded for that sends the row through the radix select and a sorting network.
 template <bool BF16>
 __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     uint64_t* buf = reinterpret_cast<uint64_t*>(sh.cand_val);   // cand_val and cand_id, back to back
-    const double dV = (double)V;
-    const double scale = (double)kBins / (((double)(key_hi - key_lo) + 1.0) * dV);
+    const uint32_t kr = key_hi - key_lo;
+    const int kb = kr ? 32 - __clz((int)kr) : 0;                 // bits of the key range
+    const int vb = V > 1 ? 32 - __clz(V - 1) : 0;                // bits of an id
+    const int ib = min(32 - kb, vb);                             // id bits that take part
+    const int id_drop = vb - ib;
+    const int cshift = max(0, kb + ib - kCoarseLog2);            // p >> cshift < kCoarse
+    static_assert(kCoarse <= kT && kCoarse % kWave == 0 && kCoarse <= kBins / 4, "coarse histogram geometry");
+    for (int i = tid; i < kCoarse; i += kT) sh.coarse[i] = 0;
     zero_hist(sh);
     if (tid == 0) { sh.maxbin = 0; sh.piv_bin = kBins - 1; sh.piv_before = n; }
     __syncthreads();
     uint64_t c[kCandPer];
-    int meta[kCandPer];                      // (bin << 16) | arrival order within the bin; -1: no candidate
+    uint32_t place[kCandPer];
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) {
         const int i = tid + j * kT;
-        c[j] = 0; meta[j] = -1;
+        c[j] = 0; place[j] = 0;
         if (i < n) {
             const uint32_t bits = sh.cand_val[i], id = sh.cand_id[i];
             c[j] = composite<BF16>(bits, id);
-            const double place = (double)(short_key<BF16>(bits) - key_lo) * dV + (double)(V - 1 - (int)id);
-            const int rbin = kBins - 1 - min((int)(place * scale), kBins - 1);   // reversed: bin 0 holds the largest
-            meta[j] = (rbin << 16) | (int)atomicAdd(&sh.hist[rbin], 1u);
+            place[j] = ib < 32 ? ((key_hi - short_key<BF16>(bits)) << ib) | (id >> id_drop) : (id >> id_drop);
+            atomicAdd(&sh.coarse[min(place[j] >> cshift, (uint32_t)(kCoarse - 1))], 1u);
+        }
+    }
+    __syncthreads();
+    // fine bins per coarse range, in proportion to its count (at least one where there is a candidate)
+    if (tid < kCoarse) {
+        const unsigned cnt = sh.coarse[tid];
+        constexpr int kShared = kBins - kCoarse - kCoarse / 2;      // leaves room for the "at least one" and for rounding
+        const unsigned nf = cnt ? max(1u, (unsigned)((float)cnt * ((float)kShared / (float)n))) : 0u;
+        const unsigned incl = wave_scan_incl(nf);
+        if (lane == kWave - 1) sh.wtot[wave] = (int)incl;
+        sh.coarse[tid] = (nf << 16) | (incl - nf);                 // first fine bin within this wave's share, for now
+    }
+    __syncthreads();
+    if (tid < kCoarse) {
+        unsigned before = 0;
+#pragma unroll
+        for (int w = 0; w < kCoarse / kWave; ++w) before += (w < wave) ? (unsigned)sh.wtot[w] : 0u;
+        sh.coarse[tid] += before;
+    }
+    __syncthreads();
+    int meta[kCandPer];                      // (fine bin << 16) | arrival order within the bin; -1: no candidate
+#pragma unroll
+    for (int j = 0; j < kCandPer; ++j) {
+        const int i = tid + j * kT;
+        meta[j] = -1;
+        if (i < n) {
+            const unsigned t = sh.coarse[min(place[j] >> cshift, (uint32_t)(kCoarse - 1))];
+            const uint32_t frac = cshift ? (place[j] << (32 - cshift)) : 0u;   // position inside the coarse range, as a 0.32 fraction
+            const int bin = (int)(t & 0xFFFFu) + (int)__umulhi(frac, t >> 16);
+            meta[j] = (bin << 16) | (int)atomicAdd(&sh.hist[bin], 1u);
         }
     }
     __syncthreads();
@@ -325,15 +368,21 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
     for (int j = 0; j < kCandPer; ++j) {
         pos[j] = k;
         if (meta[j] >= 0 && (meta[j] >> 16) <= piv) {
-            const int rbin = meta[j] >> 16;
-            const int s = (int)sh.hist[rbin];
-            const int e = rbin < piv ? (int)sh.hist[rbin + 1] : n_keep;
+            const int bin = meta[j] >> 16;
+            const int s = (int)sh.hist[bin];
+            const int e = bin < piv ? (int)sh.hist[bin + 1] : n_keep;
             int larger = 0;
-            for (int q = s; q < e; ++q) larger += buf[q] > c[j] ? 1 : 0;
+            for (int q = s; q < e; q += 4) {         // four bin-mates per round trip to LDS
+                uint64_t m[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) m[u] = buf[min(q + u, kCap - 1)];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) larger += (q + u < e && m[u] > c[j]) ? 1 : 0;
+            }
             pos[j] = s + larger;
         }
     }
-    __syncthreads();                         // all places are known before the ordered list overwrites the bins
+    __syncthreads();                         // all positions are known before the ordered list overwrites the bins
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) if (pos[j] < k) buf[pos[j]] = c[j];
     __syncthreads();
@@ -377,10 +426,17 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     const float c = 1.4426950408889634f * inv_T;
     const float qnan = __uint_as_float(0x7FC00000u);
 
+    // Row loads go through a buffer descriptor that spans the row's nq vectors: the address is the
+    // descriptor's base + a scalar offset (sub-tile, vector) + this lane's constant offset, so that no
+    // vector arithmetic forms it, and vectors behind the row read as zero (unpack masks them anyway).
+    const __amdgpu_buffer_rsrc_t row_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)rv.base, 0, nq * 16, 0x00020000);
+    const int lane_off = tid * 16;
     auto load_sub = [&](int sub, uint4 (&dst)[SV]) {
-        // vectors behind the row re-read its last vector (always a valid address); unpack masks them
 #pragma unroll
-        for (int j = 0; j < SV; ++j) dst[j] = load16_stream(rv.base + min(sub * (kT * SV) + j * kT + tid, nq - 1));
+        for (int j = 0; j < SV; ++j) {
+            const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(row_rsrc, lane_off, (sub * (kT * SV) + j * kT) * 16, 2 /* non-temporal */);
+            dst[j] = make_uint4(t.x, t.y, t.z, t.w);
+        }
     };
     // Unpack NVV vectors, vector jj being vector q0 + jj*kT of the row.  With `edge`, elements outside
     // the row (alignment prologue, tail) become NaN, which fails every admission test.
@@ -482,12 +538,78 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     using nv0_t = std::integral_constant<int, NV0>;
     using e0_t = std::integral_constant<int, E0>;
 
+    // Optimistic pass: every element above the threshold claims a slot with an LDS atomic of its own (a
+    // few lanes per instruction) and later writes (value, id) there.  Both steps are hand-issued so
+    // that they stay straight-line code (predication by EXEC, no branches for the compiler to lay
+    // out): claim_asm forms the lane mask, claims under it and hands the mask on; put_asm waits for
+    // the claimed slots and writes under the same masks, skipping columns nobody passed.  The counter
+    // counts bytes of cand_val (4 per candidate) so that a masked slot is the LDS address; slots wrap
+    // around the buffer: once the count has passed its end the pass is lost anyway.
+    typedef __attribute__((address_space(3))) unsigned lds_u32;
+    const unsigned cnt_addr = (unsigned)(uintptr_t)(lds_u32*)&sh.cnt;
+    const unsigned val_addr = (unsigned)(uintptr_t)(lds_u32*)&sh.cand_val[0];
+    unsigned four = 4u, wrap = (unsigned)(kCap * 4 - 4);
+    asm volatile("" : "+v"(four), "+v"(wrap));
+    auto claim_asm = [&, four](auto ee_tag, const float* v, float tau, int* slot, unsigned long long* passed) {
+        constexpr int EE = decltype(ee_tag)::value;
+        unsigned ca = cnt_addr;
+        asm volatile("" : "+v"(ca));
+#pragma unroll
+        for (int e = 0; e < EE; ++e) {
+            unsigned long long saved;
+            asm volatile("v_cmp_gt_f32_e64 %[m], %[x], %[t]\n\t"
+                         "s_and_saveexec_b64 %[sv], %[m]\n\t"
+                         "ds_add_rtn_u32 %[slot], %[ca], %[four]\n\t"
+                         "s_mov_b64 exec, %[sv]"
+                         : [slot] "=&v"(slot[e]), [m] "=&s"(passed[e]), [sv] "=&s"(saved)
+                         : [x] "v"(v[e]), [t] "v"(tau), [ca] "v"(ca), [four] "v"(four)
+                         : "memory");
+        }
+    };
+    auto put_asm = [&, wrap](auto nvv_tag, const float* v, int* slot, const unsigned long long* passed, int x0) {
+        constexpr int NVV = decltype(nvv_tag)::value;
+        static_assert(NVV == 2 || NVV == 4, "the wait names every slot");
+        // the claimed slots have arrived (the running sum is named so that the statistics stay in front)
+        if constexpr (NVV * N == 8)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]), "+v"(slot[3]),
+                         "+v"(slot[4]), "+v"(slot[5]), "+v"(slot[6]), "+v"(slot[7]), "+v"(os.s));
+        else {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]), "+v"(slot[3]),
+                         "+v"(slot[4]), "+v"(slot[5]), "+v"(slot[6]), "+v"(slot[7]), "+v"(os.s));
+            asm volatile("" : "+v"(slot[8]), "+v"(slot[9]), "+v"(slot[10]), "+v"(slot[11]),
+                         "+v"(slot[12]), "+v"(slot[13]), "+v"(slot[14]), "+v"(slot[15]));
+        }
+        const unsigned va = val_addr;
+#pragma unroll
+        for (int j = 0; j < NVV; ++j)
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                unsigned long long saved;
+                unsigned at, id;
+                asm volatile("s_and_saveexec_b64 %[sv], %[m]\n\t"
+                             "s_cbranch_execz .Lskip%=\n\t"
+                             "v_and_b32 %[at], %[slot], %[wrap]\n\t"
+                             "v_add_u32 %[at], %[va], %[at]\n\t"
+                             "v_add_u32 %[id], %[c], %[x0]\n\t"
+                             "ds_write2st64_b32 %[at], %[x], %[id] offset1:128\n"
+                             ".Lskip%=:\n\t"
+                             "s_mov_b64 exec, %[sv]"
+                             : [sv] "=&s"(saved), [at] "=&v"(at), [id] "=&v"(id)
+                             : [m] "s"(passed[j * N + e]), [slot] "v"(slot[j * N + e]), [wrap] "v"(wrap), [va] "s"(va),
+                               [c] "s"(j * kT * N + e), [x0] "v"(x0), [x] "v"(v[j * N + e])
+                             : "memory");
+            }
+    };
+    static_assert(offsetof(CompressShared, cand_id) - offsetof(CompressShared, cand_val) == 128 * 64 * 4,
+                  "ds_write2st64 offset1:128 reaches cand_id from cand_val");
+
     const bool more = n_sub > T0;                // the row goes on behind the sample
     const int n0 = min(V, SAMPLE - rv.o);        // row elements in the sample
     const int r_opt = more ? optimistic_rank(k, V, n0) : 0;
     float M = kNegInf;
     double S = 0.0;
     uint32_t key_lo = 0, key_hi = 0;
+    int n_held = -1;                             // candidates held at the end of the row (-1: read the counter)
 
     for (int attempt = r_opt > 0 ? 0 : 1; attempt < 2; ++attempt) {
         const bool optimistic = attempt == 0;
@@ -548,8 +670,15 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             }
             if (admit_all && more) key_lo = 0;   // later sub-tiles may go below the sample's minimum
             __syncthreads();
-            const int failed_at = append(nv0_t{}, v, tau, admit_all, tid * N - rv.o);
-            if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: the sample fits the empty buffer
+            if (!optimistic) {
+                const int failed_at = append(nv0_t{}, v, tau, admit_all, tid * N - rv.o);
+                if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: the sample fits the empty buffer
+            } else if (!admit_all) {
+                int slot[E0];
+                unsigned long long passed[E0];
+                claim_asm(e0_t{}, v, tau, slot, passed);
+                put_asm(nv0_t{}, v, slot, passed, tid * N - rv.o);
+            }
         }
 
         bool enough = true;
@@ -561,48 +690,25 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             if (applies) {
 #pragma unroll
                 for (int t = 0; t < T0; ++t) load_sub(RING + t, rb[t]);
-                // Every element above the threshold claims a slot with an LDS atomic of its own (a few lanes
-                // per instruction); the statistics sit between the claims and the writes that need the
-                // slots.  A claim at or behind the end of the buffer writes nothing: the count tells.
-                typedef __attribute__((address_space(3))) int lds_int;
-                lds_int* cnt_lds = (lds_int*)&sh.cnt;
-                asm volatile("" : "+v"(cnt_lds));                   // the counter's address stays in one register
-                auto claim = [&](const float* v, int* slot) {
-#pragma unroll
-                    for (int e = 0; e < ES; ++e)
-                        if (v[e] > tau) slot[e] = __hip_atomic_fetch_add(cnt_lds, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                };
-                // Slots wrap around the buffer: once the count has passed its end the pass is lost anyway.
-                auto put = [&](const float* v, const int* slot, int x0) {
-#pragma unroll
-                    for (int j = 0; j < SV; ++j)
-#pragma unroll
-                        for (int e = 0; e < N; ++e)
-                            if (v[j * N + e] > tau) {
-                                int at = slot[j * N + e];
-                                asm volatile("" : "+v"(at));        // the mask stays here, behind the statistics
-                                at &= kCap - 1;
-                                sh.cand_val[at] = __float_as_uint(v[j * N + e]);
-                                sh.cand_id[at] = (unsigned)(x0 + j * kT * N + e);
-                            }
-                };
                 auto full = [&](int sub, uint4 (&buf)[SV]) {        // a sub-tile wholly inside the row
                     float v[ES];
                     int slot[ES];
+                    unsigned long long passed[ES];
                     unpack_vecs(sv_t{}, 0, buf, v, false);
-                    claim(v, slot);
+                    claim_asm(es_t{}, v, tau, slot, passed);
                     add_stats(es_t{}, v, false);
-                    put(v, slot, sub * SUB - rv.o + tid * N);
+                    put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     load_sub(sub + RING, buf);
                 };
                 auto ragged = [&](int sub, uint4 (&buf)[SV]) {      // any sub-tile: what lies behind the row is masked
                     if (sub < n_sub) {
                         float v[ES];
                         int slot[ES];
+                        unsigned long long passed[ES];
                         unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, true);
-                        claim(v, slot);
+                        claim_asm(es_t{}, v, tau, slot, passed);
                         add_stats(es_t{}, v, true);
-                        put(v, slot, sub * SUB - rv.o + tid * N);
+                        put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     }
                 };
                 // the hot loop holds nothing but the common case, RING times (one copy per buffer role)
@@ -615,7 +721,9 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                 for (int r = 0; r < RING; ++r) ragged(sub + r, rb[(T0 + r) % RING]);
             }
             __syncthreads();
-            enough = applies && !sh.overflowed && sh.cnt >= k && sh.cnt <= kCap;
+            const int held = sh.cnt >> 2;        // (this pass counts bytes of cand_val)
+            enough = applies && !sh.overflowed && held >= k && held <= kCap;
+            n_held = enough ? held : -1;
             __syncthreads();                     // everyone has read the verdict before the next attempt resets it
         } else {
             // ---- behind the sample, safe: all waves meet after every sub-tile; a full buffer is pruned back to
@@ -683,7 +791,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     }
 
     // ---- exact cut to k, ordering and emission
-    const int n_held = sh.cnt;
+    if (n_held < 0) n_held = sh.cnt;
     const int n = min(n_held, k);
     const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi);
 
