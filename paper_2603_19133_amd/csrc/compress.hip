@@ -802,18 +802,32 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     int my_count = 0;
     int32_t* idx_row = idx + row * (int64_t)k;
     float* prob_row = prob + row * (int64_t)k;
-    for (int j0 = 0; j0 < k; j0 += kT) {
-        const int slot = j0 + tid;
-        int id = -1;
-        float pr = 0.f;
-        if (slot < n) {
-            const uint64_t cv = sorted[slot];
-            id = (int)(kIdMask - ((uint32_t)cv & kIdMask));
-            const float x = __uint_as_float(bits_of_short_key<BF16>((uint32_t)(cv >> kIdBits)));
-            pr = (float)(exp_emit(x, M, cd) * invS);
+    auto emit_value = [&](int slot, int& id, float& pr) {
+        const uint64_t cv = sorted[slot];
+        id = (int)(kIdMask - ((uint32_t)cv & kIdMask));
+        const float x = __uint_as_float(bits_of_short_key<BF16>((uint32_t)(cv >> kIdBits)));
+        pr = (float)(exp_emit(x, M, cd) * invS);
+    };
+    if (!use_top_p) {
+        // every slot is independent: unrolled, so that the LDS reads, the exponentials and the stores of
+        // the kSortPer slots of a thread overlap
+#pragma unroll
+        for (int j = 0; j < kSortPer; ++j) {
+            const int slot = tid + j * kT;
+            if (slot < k) {
+                int id = -1;
+                float pr = 0.f;
+                if (slot < n) { emit_value(slot, id, pr); my_mass += (double)pr; ++my_count; }
+                idx_row[slot] = id;
+                prob_row[slot] = pr;
+            }
         }
-        bool keep = slot < n;
-        if (use_top_p) {   // keep a slot iff the probability before it has not reached top_p
+    } else {
+        for (int j0 = 0; j0 < k; j0 += kT) {   // keep a slot iff the probability before it has not reached top_p
+            const int slot = j0 + tid;
+            int id = -1;
+            float pr = 0.f;
+            if (slot < n) emit_value(slot, id, pr);
             const double mine = (double)pr;
             const double incl = wave_scan_incl(mine);
             if (lane == kWave - 1) sh.red[wave] = incl;
@@ -822,14 +836,14 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
 #pragma unroll
             for (int w = 0; w < kW; ++w) { const double t = sh.red[w]; if (w < wave) before += t; tot += t; }
             __syncthreads();
-            keep = keep && (before + incl - mine) < (double)top_p;
+            const bool keep = slot < n && (before + incl - mine) < (double)top_p;
             carry += tot;
+            if (slot < k) {
+                idx_row[slot] = keep ? id : -1;
+                prob_row[slot] = keep ? pr : 0.f;
+            }
+            if (keep) { my_mass += (double)pr; ++my_count; }
         }
-        if (slot < k) {
-            idx_row[slot] = keep ? id : -1;
-            prob_row[slot] = keep ? pr : 0.f;
-        }
-        if (keep) { my_mass += (double)pr; ++my_count; }
     }
     const double wm = wave_sum(my_mass);
     const int wc = wave_sum(my_count);
