@@ -1,12 +1,13 @@
 // Correction / bonus token (paper Section 3.3): one draw per sequence from
 // norm(max(0, P_j - qhat_j)) by inverse CDF in ascending vocabulary id.
 //
-// One workgroup per sequence streams target row j once.  The sparse qhat of the matching draft
-// row is scattered into an LDS image of the current tile, so the dense pass sees qhat(x) at LDS
-// speed.  Each wave leaves one partial sum per 16-byte-vector column it owns ("segment": 64 lanes
-// x 4 or 8 consecutive ids per lane, contiguous in id); segment sums are kept in LDS in id order.
-// The crossing of u*R is then located among the segments and only that one segment (1 KB) is read
-// again to name the token.
+// One workgroup per sequence streams target row j once, in tiles of 16384 elements.  The sparse qhat
+// of the matching draft row is scattered into an LDS image of the tile, so the dense pass sees
+// qhat(x) at LDS speed; two images alternate, and instead of clearing an image the entries written
+// for a tile are taken back after it, so that an image costs k writes per row, not V.  Within a tile
+// each wave owns 1024 consecutive ids (a "segment") and leaves one partial sum per segment; the
+// segment sums are kept in LDS in id order.  The crossing of u*R is then located among the segments
+// and only that one segment (4 KB at most) is read again to name the token.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -15,11 +16,12 @@ namespace picospec {
 namespace {
 
 constexpr int kTile = 16384;                                  // elements per tile (both dtypes)
+constexpr int kSegLen = kTile / kWaves;                       // 1024 consecutive ids per wave and tile
 constexpr int kMaxTiles = (kMaxV + 16) / kTile + 1;
-constexpr int kMaxSeg = kMaxTiles * 4 * kWaves;               // fp32: 4 vector columns per tile
+constexpr int kMaxSeg = kMaxTiles * kWaves;
 
 struct __align__(16) ResidualShared {
-    float qtile[kTile];         // qhat image of the current tile (0 off-support)
+    float qimg[2][kTile];       // qhat images of two consecutive tiles (0 off-support)
     double seg[kMaxSeg];        // residual mass of each segment, id order
     double red[2 * kWaves];
     double before;              // cumulative residual in front of the chosen segment
@@ -40,8 +42,10 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     ResidualShared& sh = *reinterpret_cast<ResidualShared*>(smem_raw);
-    constexpr int N = Vec<BF16>::N, NV = kTile / (kThreads * N);
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    constexpr int N = Vec<BF16>::N, NV = kTile / (kThreads * N);      // vectors per thread and tile
+    constexpr int kSegVec = NV * kWave;                                // vectors per segment
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: it forms scalar load offsets
     const int b = blockIdx.x;
     const int d0 = seq_off[b];
     int g = seq_off[b + 1] - d0;
@@ -64,15 +68,24 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     const float c = 1.4426950408889634f * inv_T;
     const RowView rv = row_view<BF16>(tgt_logits, ld, rt, V);
     const int n_tiles = (rv.L + kTile - 1) / kTile;
-    const int n_seg = n_tiles * NV * kWaves;
+    const int n_seg = n_tiles * kWaves;
     const int32_t* ids = q_idx + rd * k;
     const float* qp = q_prob + rd * k;
+    const int nq = (rv.L + N - 1) / N;
+    // row loads: descriptor base + scalar offset of the vector group + this lane's offset; vectors
+    // behind the row read as zero and are masked
+    const __amdgpu_buffer_rsrc_t row_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)rv.base, 0, nq * 16, 0x00020000);
+    // vector `first + lane` of the row (first is uniform across the wave)
+    auto load_vec = [&](int first) {
+        const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(row_rsrc, lane * 16, first * 16, 2 /* non-temporal */);
+        return make_uint4(t.x, t.y, t.z, t.w);
+    };
 
     // residual of the N elements of the 16-byte vector `raw` = vector q of the row, given the qhat image
-    auto residual_of = [&](const uint4& raw, int q, const float* qimg, float (&r)[N]) {
+    auto residual_of = [&](const uint4& raw, int q, const float* qimg, bool edge, float (&r)[N]) {
         float v[N];
         unpack<BF16>(raw, v);
-        const unsigned vm = vec_valid_mask<BF16>(rv, q);
+        const unsigned vm = edge ? vec_valid_mask<BF16>(rv, q) : 0xFFFFFFFFu;
 #pragma unroll
         for (int e = 0; e < N; ++e) {
             const float p = exp_stream(v[e], M, c) * invS;
@@ -80,8 +93,6 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
             r[e] = ((vm >> e) & 1u) && d > 0.f ? d : 0.f;
         }
     };
-    const int nq = (rv.L + N - 1) / N;
-    auto load_vec = [&](int q) { return load16_stream(rv.base + min(q, nq - 1)); };   // behind the row: its last vector, masked later
 
     // this thread's share of the sparse record (k <= kMaxK), kept in registers across tiles
     constexpr int SP = kMaxK / kThreads;
@@ -94,40 +105,55 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         my_q[z] = 0.f;
         if (s < cnt) { my_id[z] = ids[s]; my_q[z] = qp[s] * q_scale; }
     }
+    // write (or take back) this thread's record entries that fall into ids [lo, lo + len)
+    auto scatter = [&](float* img, int lo, int len, bool take_back) {
+#pragma unroll
+        for (int z = 0; z < SP; ++z) {
+            const int off = my_id[z] - lo;
+            if (my_id[z] >= 0 && off >= 0 && off < len) img[off] = take_back ? 0.f : my_q[z];
+        }
+    };
 
+    {   // both images start empty
+        float4* z4 = reinterpret_cast<float4*>(&sh.qimg[0][0]);
+#pragma unroll
+        for (int z = 0; z < 2 * kTile / 4 / kThreads; ++z) z4[z * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __syncthreads();
+
+    // vector of (tile it, wave, jv, lane): it * (kThreads * NV) + wave * kSegVec + jv * kWave + lane
+    const int wave_vec = wave * kSegVec;
     double R = 0.0;
     for (int attempt = 0; attempt < 2; ++attempt) {
         uint4 cur[NV], nxt[NV];
 #pragma unroll
-        for (int jv = 0; jv < NV; ++jv) cur[jv] = load_vec(jv * kThreads + tid);
+        for (int jv = 0; jv < NV; ++jv) cur[jv] = load_vec(wave_vec + jv * kWave);
+        if (has_q) scatter(sh.qimg[0], -rv.o, kTile, false);
+        __syncthreads();
         for (int it = 0; it < n_tiles; ++it) {
             if (it + 1 < n_tiles) {
 #pragma unroll
-                for (int jv = 0; jv < NV; ++jv) nxt[jv] = load_vec((it + 1) * (kThreads * NV) + jv * kThreads + tid);
+                for (int jv = 0; jv < NV; ++jv) nxt[jv] = load_vec((it + 1) * (kThreads * NV) + wave_vec + jv * kWave);
             }
-            // qhat image of this tile
-            float4* qt4 = reinterpret_cast<float4*>(sh.qtile);
-#pragma unroll
-            for (int z = 0; z < kTile / 4 / kThreads; ++z) qt4[z * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
-            __syncthreads();
-            if (has_q) {
-                const int lo = it * kTile - rv.o;            // id of the tile's first virtual element
-#pragma unroll
-                for (int z = 0; z < SP; ++z) {
-                    const int off = my_id[z] - lo;
-                    if (my_id[z] >= 0 && off >= 0 && off < kTile) sh.qtile[off] = my_q[z];
-                }
-            }
-            __syncthreads();
+            const float* img = sh.qimg[it & 1];
+            const bool edge = it == 0 || it + 1 == n_tiles;
+            double sum = 0.0;
 #pragma unroll
             for (int jv = 0; jv < NV; ++jv) {
                 float r[N];
-                residual_of(cur[jv], it * (kThreads * NV) + jv * kThreads + tid, sh.qtile + (jv * kThreads + tid) * N, r);
-                double sum = 0.0;
+                const int ql = wave_vec + jv * kWave + lane;             // vector within the tile
+                residual_of(cur[jv], it * (kThreads * NV) + ql, img + ql * N, edge, r);
+                float part = 0.f;
 #pragma unroll
-                for (int e = 0; e < N; ++e) sum += (double)r[e];
-                sum = wave_sum(sum);
-                if (lane == 0) sh.seg[(it * NV + jv) * kWaves + wave] = sum;
+                for (int e = 0; e < N; ++e) part += r[e];
+                sum += (double)part;
+            }
+            sum = wave_sum(sum);
+            if (lane == 0) sh.seg[it * kWaves + wave] = sum;
+            __syncthreads();                                             // the image of this tile has been read
+            if (has_q) {
+                scatter(sh.qimg[it & 1], it * kTile - rv.o, kTile, true);
+                if (it + 1 < n_tiles) scatter(sh.qimg[(it + 1) & 1], (it + 1) * kTile - rv.o, kTile, false);
             }
             __syncthreads();
 #pragma unroll
@@ -177,60 +203,56 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     const bool crossed = pick != 0x7FFFFFFF;
     if (!crossed) pick = sh.seg_last < 0 ? 0 : sh.seg_last;   // rounding: last segment with mass
     if (crossed && my_pick == pick) sh.before = cum;          // exactly one thread owns the chosen segment
+    // (both images are empty again: every entry was taken back after its tile)
+    const int it = pick / kWaves, pw = pick % kWaves;
+    const int seg_vec = it * (kThreads * NV) + pw * kSegVec;  // first vector of the segment
+    const int seg_lo = seg_vec * N - rv.o;                    // id of its first element
+    if (has_q) scatter(sh.qimg[0], seg_lo, kSegLen, false);
     __syncthreads();
 
-    // re-read that one segment and name the token (wave 0)
-    const int col = pick / kWaves, pw = pick % kWaves, it = col / NV, jv = col % NV;
-    const int seg_lo = (it * (kThreads * NV) + jv * kThreads + pw * kWave) * N - rv.o;   // id of the segment's first element
+    // re-read that one segment and name the token (wave 0): ids ascend with (jv, lane, element)
     if (wave == 0) {
+        const double base0 = sh.before;
+        double base = base0;
+        int tok = -1, last_tok = -1;
 #pragma unroll
-        for (int e = 0; e < N; ++e) sh.qtile[lane * N + e] = 0.f;
-    }
-    __syncthreads();
-    if (has_q) {
+        for (int jv = 0; jv < NV; ++jv) {
+            float r[N];
+            const int ql = jv * kWave + lane;
+            residual_of(load_vec(seg_vec + jv * kWave), seg_vec + ql, sh.qimg[0] + ql * N, true, r);
+            double sum = 0.0;
 #pragma unroll
-        for (int z = 0; z < SP; ++z) {
-            const int off = my_id[z] - seg_lo;
-            if (my_id[z] >= 0 && off >= 0 && off < kWave * N) sh.qtile[off] = my_q[z];
-        }
-    }
-    __syncthreads();
-    if (wave == 0) {
-        float r[N];
-        const int qv = it * (kThreads * NV) + jv * kThreads + pw * kWave + lane;
-        residual_of(load_vec(qv), qv, sh.qtile + lane * N, r);
-        double sum = 0.0;
+            for (int e = 0; e < N; ++e) sum += (double)r[e];
+            const double inc = wave_scan_incl(sum);
+            const unsigned long long hit = (crossed && tok < 0) ? __ballot(base + inc > target) : 0ull;
+            if (hit) {
+                const int owner = __ffsll((long long)hit) - 1;
+                int t = -1;
+                if (lane == owner) {
+                    double cu = base + inc - sum;
 #pragma unroll
-        for (int e = 0; e < N; ++e) sum += (double)r[e];
-        const double inc = wave_scan_incl(sum);
-        const double base = sh.before;
-        int tok = -1;
-        const unsigned long long hit = crossed ? __ballot(base + inc > target) : 0ull;
-        if (hit) {
-            const int owner = __ffsll((long long)hit) - 1;
-            if (lane == owner) {
-                double cu = base + inc - sum;
-#pragma unroll
-                for (int e = 0; e < N; ++e) {
-                    cu += (double)r[e];
-                    if (tok < 0 && cu > target) tok = seg_lo + lane * N + e;
+                    for (int e = 0; e < N; ++e) {
+                        cu += (double)r[e];
+                        if (t < 0 && cu > target) t = seg_lo + ql * N + e;
+                    }
+                    if (t < 0) t = seg_lo + ql * N + N - 1;
                 }
-                if (tok < 0) tok = seg_lo + lane * N + N - 1;
+                tok = __shfl(t, owner, kWave);
             }
-            tok = __shfl(tok, owner, kWave);
-        } else {   // rounding: the last id of the segment with residual mass
+            // rounding fallback: the last id of the segment with residual mass
             const unsigned long long any = __ballot(sum > 0.0);
             if (any) {
                 const int owner = 63 - __clzll((long long)any);
+                int t = -1;
                 if (lane == owner) {
 #pragma unroll
-                    for (int e = 0; e < N; ++e) if (r[e] > 0.f) tok = seg_lo + lane * N + e;
+                    for (int e = 0; e < N; ++e) if (r[e] > 0.f) t = seg_lo + ql * N + e;
                 }
-                tok = __shfl(tok, owner, kWave);
-            } else {
-                tok = min(max(seg_lo, 0), V - 1);
+                last_tok = __shfl(t, owner, kWave);
             }
+            base += __shfl(inc, kWave - 1, kWave);
         }
+        if (tok < 0) tok = last_tok >= 0 ? last_tok : min(max(seg_lo, 0), V - 1);
         if (lane == 0) {
             out_tok[b] = tok;
             resid_mass[b] = (fl & 4u) ? 0.f : (float)R;
