@@ -64,7 +64,6 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         if (renorm) q_scale = 1.f / q_mass[rd];
     }
     const float M = tgt_max[rt];
-    const float invS = 1.f / tgt_sum[rt];
     const float c = 1.4426950408889634f * inv_T;
     const RowView rv = row_view<BF16>(tgt_logits, ld, rt, V);
     const int n_tiles = (rv.L + kTile - 1) / kTile;
@@ -81,16 +80,27 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         return make_uint4(t.x, t.y, t.z, t.w);
     };
 
+    // P(x) = 2^(z*c + kappa), kappa = -M*c - log2 S, so that one fused multiply-add and one exponential
+    // form each probability.  kappa is rounded to fp32 once; that would scale every P by the same
+    // factor 1 + eps, so qhat is scaled by it as well (the residuals then all carry it) and the sums
+    // are divided by it at the end: the arithmetic stays that of P - qhat.
+    const double kappa_d = -(double)M * (double)c - log2((double)tgt_sum[rt]);
+    const float kappa = (float)kappa_d;
+    const double common = exp2((double)kappa - kappa_d);       // 1 + eps
     // residual of the N elements of the 16-byte vector `raw` = vector q of the row, given the qhat image
     auto residual_of = [&](const uint4& raw, int q, const float* qimg, bool edge, float (&r)[N]) {
         float v[N];
         unpack<BF16>(raw, v);
-        const unsigned vm = edge ? vec_valid_mask<BF16>(rv, q) : 0xFFFFFFFFu;
+        if (edge) {
+            const unsigned vm = vec_valid_mask<BF16>(rv, q);
 #pragma unroll
-        for (int e = 0; e < N; ++e) {
-            const float p = exp_stream(v[e], M, c) * invS;
-            const float d = p - qimg[e];
-            r[e] = ((vm >> e) & 1u) && d > 0.f ? d : 0.f;
+            for (int e = 0; e < N; ++e) {
+                const float d = __builtin_amdgcn_exp2f(fmaf(v[e], c, kappa)) - qimg[e];
+                r[e] = ((vm >> e) & 1u) && d > 0.f ? d : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < N; ++e) r[e] = fmaxf(__builtin_amdgcn_exp2f(fmaf(v[e], c, kappa)) - qimg[e], 0.f);
         }
     };
 
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         const int s = z * kThreads + tid;
         my_id[z] = -1;
         my_q[z] = 0.f;
-        if (s < cnt) { my_id[z] = ids[s]; my_q[z] = qp[s] * q_scale; }
+        if (s < cnt) { my_id[z] = ids[s]; my_q[z] = (float)((double)qp[s] * (double)q_scale * common); }
     }
     // write (or take back) this thread's record entries that fall into ids [lo, lo + len)
     auto scatter = [&](float* img, int lo, int len, bool take_back) {
@@ -125,16 +135,18 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     const int wave_vec = wave * kSegVec;
     double R = 0.0;
     for (int attempt = 0; attempt < 2; ++attempt) {
-        uint4 cur[NV], nxt[NV];
+        // three tiles in registers: one in use, two in flight (loads behind the row read zeros)
+        uint4 tb[3][NV];
+        auto load_tile = [&](int it, uint4 (&dst)[NV]) {
 #pragma unroll
-        for (int jv = 0; jv < NV; ++jv) cur[jv] = load_vec(wave_vec + jv * kWave);
+            for (int jv = 0; jv < NV; ++jv) dst[jv] = load_vec(it * (kThreads * NV) + wave_vec + jv * kWave);
+        };
+        load_tile(0, tb[0]);
+        load_tile(1, tb[1]);
+        load_tile(2, tb[2]);
         if (has_q) scatter(sh.qimg[0], -rv.o, kTile, false);
         __syncthreads();
-        for (int it = 0; it < n_tiles; ++it) {
-            if (it + 1 < n_tiles) {
-#pragma unroll
-                for (int jv = 0; jv < NV; ++jv) nxt[jv] = load_vec((it + 1) * (kThreads * NV) + wave_vec + jv * kWave);
-            }
+        auto step = [&](int it, uint4 (&buf)[NV]) {
             const float* img = sh.qimg[it & 1];
             const bool edge = it == 0 || it + 1 == n_tiles;
             double sum = 0.0;
@@ -142,12 +154,13 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
             for (int jv = 0; jv < NV; ++jv) {
                 float r[N];
                 const int ql = wave_vec + jv * kWave + lane;             // vector within the tile
-                residual_of(cur[jv], it * (kThreads * NV) + ql, img + ql * N, edge, r);
+                residual_of(buf[jv], it * (kThreads * NV) + ql, img + ql * N, edge, r);
                 float part = 0.f;
 #pragma unroll
                 for (int e = 0; e < N; ++e) part += r[e];
                 sum += (double)part;
             }
+            load_tile(it + 3, buf);
             sum = wave_sum(sum);
             if (lane == 0) sh.seg[it * kWaves + wave] = sum;
             __syncthreads();                                             // the image of this tile has been read
@@ -156,9 +169,17 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
                 if (it + 1 < n_tiles) scatter(sh.qimg[(it + 1) & 1], (it + 1) * kTile - rv.o, kTile, false);
             }
             __syncthreads();
-#pragma unroll
-            for (int jv = 0; jv < NV; ++jv) cur[jv] = nxt[jv];
+        };
+        // (whole groups of three in the loop, so that its body has one path and the waits for the loads
+        // in flight stay exact; the last one or two tiles follow it)
+        int it = 0;
+        for (; it + 3 <= n_tiles; it += 3) {
+            step(it, tb[0]);
+            step(it + 1, tb[1]);
+            step(it + 2, tb[2]);
         }
+        if (it < n_tiles) step(it, tb[0]);
+        if (it + 1 < n_tiles) step(it + 1, tb[1]);
         // total residual mass
         double part = 0.0;
         for (int s = tid; s < n_seg; s += kThreads) part += sh.seg[s];
@@ -169,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) R += sh.red[w];
         __syncthreads();
-        if (R > 0.0 || !has_q) break;
+        if (R > 0.0 || !has_q) break;   // (R still carries the common factor)
         // P == qhat numerically: draw from P itself
         fl |= 4u;
         has_q = false;
@@ -204,8 +225,8 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     if (!crossed) pick = sh.seg_last < 0 ? 0 : sh.seg_last;   // rounding: last segment with mass
     if (crossed && my_pick == pick) sh.before = cum;          // exactly one thread owns the chosen segment
     // (both images are empty again: every entry was taken back after its tile)
-    const int it = pick / kWaves, pw = pick % kWaves;
-    const int seg_vec = it * (kThreads * NV) + pw * kSegVec;  // first vector of the segment
+    const int pt = pick / kWaves, pw = pick % kWaves;
+    const int seg_vec = pt * (kThreads * NV) + pw * kSegVec;  // first vector of the segment
     const int seg_lo = seg_vec * N - rv.o;                    // id of its first element
     if (has_q) scatter(sh.qimg[0], seg_lo, kSegLen, false);
     __syncthreads();
@@ -255,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         if (tok < 0) tok = last_tok >= 0 ? last_tok : min(max(seg_lo, 0), V - 1);
         if (lane == 0) {
             out_tok[b] = tok;
-            resid_mass[b] = (fl & 4u) ? 0.f : (float)R;
+            resid_mass[b] = (fl & 4u) ? 0.f : (float)(R / common);
             flags[b] = fl;
         }
     }
