@@ -700,14 +700,15 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                     put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     load_sub(sub + RING, buf);
                 };
-                auto ragged = [&](int sub, uint4 (&buf)[SV]) {      // any sub-tile: what lies behind the row is masked
+                auto ragged = [&](int sub, uint4 (&buf)[SV]) {      // the last sub-tiles: what lies behind the row is masked
                     if (sub < n_sub) {
                         float v[ES];
                         int slot[ES];
                         unsigned long long passed[ES];
-                        unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, true);
+                        const bool edge = sub + 1 == n_sub;
+                        unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, edge);
                         claim_asm(es_t{}, v, tau, slot, passed);
-                        add_stats(es_t{}, v, true);
+                        add_stats(es_t{}, v, edge);
                         put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     }
                 };

@@ -71,7 +71,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
 }
 
 // One workgroup (16 waves) per sequence, one wave per draft position.  The wave looks the drafted
-// token up in the position's sparse record with 16-byte loads (four in flight per lane).
+// token up in the position's sparse record with 16-byte loads (four in flight per lane), front
+// first, and stops once it is found.
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void accept_kernel(
     const void* __restrict__ tgt_logits, int64_t ld, int V, float inv_T, int B,
@@ -114,23 +115,38 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
             cnt = cnt < 0 ? 0 : (cnt > k ? k : cnt);
             const int32_t* ids = q_idx + rd * k;
             int slot = -1;
+            // The record is ordered by probability and the token was drawn from it, so it sits near the
+            // front more often than not: the scan goes in rounds of 1024 ids and stops at the round
+            // that holds it.
             if ((((uintptr_t)ids) & 15u) == 0) {
                 const int4* ids4 = reinterpret_cast<const int4*>(ids);
                 const int n4 = cnt >> 2;
-#pragma unroll 4
-                for (int s = lane; s < n4; s += kWave) {
-                    const int4 q = ids4[s];
-                    if (q.x == x) slot = 4 * s;
-                    if (q.y == x) slot = 4 * s + 1;
-                    if (q.z == x) slot = 4 * s + 2;
-                    if (q.w == x) slot = 4 * s + 3;
+                for (int s0 = 0; s0 < n4; s0 += 4 * kWave) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int s = s0 + u * kWave + lane;
+                        if (s < n4) {
+                            const int4 q = ids4[s];
+                            if (q.x == x) slot = 4 * s;
+                            if (q.y == x) slot = 4 * s + 1;
+                            if (q.z == x) slot = 4 * s + 2;
+                            if (q.w == x) slot = 4 * s + 3;
+                        }
+                    }
+                    if (__ballot(slot >= 0)) break;
                 }
-                for (int s = 4 * n4 + lane; s < cnt; s += kWave)
-                    if (ids[s] == x) slot = s;
+                if (!__ballot(slot >= 0))
+                    for (int s = 4 * n4 + lane; s < cnt; s += kWave)
+                        if (ids[s] == x) slot = s;
             } else {
-#pragma unroll 8
-                for (int s = lane; s < cnt; s += kWave)
-                    if (ids[s] == x) slot = s;
+                for (int s0 = 0; s0 < cnt; s0 += 8 * kWave) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int s = s0 + u * kWave + lane;
+                        if (s < cnt && ids[s] == x) slot = s;
+                    }
+                    if (__ballot(slot >= 0)) break;
+                }
             }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) slot = max(slot, __shfl_xor(slot, o, kWave));
