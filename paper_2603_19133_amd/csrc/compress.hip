@@ -809,9 +809,32 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         const float x = __uint_as_float(bits_of_short_key<BF16>((uint32_t)(cv >> kIdBits)));
         pr = (float)(exp_emit(x, M, cd) * invS);
     };
-    if (!use_top_p) {
-        // every slot is independent: unrolled, so that the LDS reads, the exponentials and the stores of
-        // the kSortPer slots of a thread overlap
+    const bool rows_aligned = (k & 3) == 0 && ((((uintptr_t)idx_row) | ((uintptr_t)prob_row)) & 15u) == 0;
+    if (!use_top_p && rows_aligned) {
+        // every slot is independent.  A thread takes four consecutive slots and writes them with one
+        // 16-byte store per array; the record is not read again by this kernel: non-temporal stores.
+        static_assert(kSortPer % 4 == 0, "four slots per thread and step");
+#pragma unroll
+        for (int j = 0; j < kSortPer / 4; ++j) {
+            const int s0 = 4 * (tid + j * kT);
+            if (s0 < k) {
+                typedef int i32x4_t __attribute__((ext_vector_type(4)));
+                typedef float f32x4_t __attribute__((ext_vector_type(4)));
+                i32x4_t ids = {-1, -1, -1, -1};
+                f32x4_t prs = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (s0 + e < n) {
+                        int id; float pr;
+                        emit_value(s0 + e, id, pr);
+                        ids[e] = id; prs[e] = pr;
+                        my_mass += (double)pr; ++my_count;
+                    }
+                __builtin_nontemporal_store(ids, reinterpret_cast<i32x4_t*>(idx_row + s0));
+                __builtin_nontemporal_store(prs, reinterpret_cast<f32x4_t*>(prob_row + s0));
+            }
+        }
+    } else if (!use_top_p) {
 #pragma unroll
         for (int j = 0; j < kSortPer; ++j) {
             const int slot = tid + j * kT;
@@ -819,8 +842,8 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                 int id = -1;
                 float pr = 0.f;
                 if (slot < n) { emit_value(slot, id, pr); my_mass += (double)pr; ++my_count; }
-                idx_row[slot] = id;
-                prob_row[slot] = pr;
+                __builtin_nontemporal_store(id, &idx_row[slot]);
+                __builtin_nontemporal_store(pr, &prob_row[slot]);
             }
         }
     } else {
