@@ -244,6 +244,13 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
     __syncthreads();
 }
 
+// Clears what order_top_k counts in; a barrier must lie between this and the call.
+__device__ __forceinline__ void order_prepare(CompressShared& sh, int n) {
+    for (int i = threadIdx.x; i < kCoarse; i += kT) sh.coarse[i] = 0;
+    zero_hist(sh);
+    if (threadIdx.x == 0) { sh.maxbin = 0; sh.piv_bin = kBins - 1; sh.piv_before = n; }
+}
+
 // Cut the n <= kCap candidates in the buffer to the min(n, k) largest by composite and order them,
 // descending; every candidate's short key lies in [key_lo, key_hi].  Returns the LDS array that
 // holds the ordered composites.  A histogram rank sort does both jobs, on candidates held in
@@ -270,10 +277,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
     const int id_drop = vb - ib;
     const int cshift = max(0, kb + ib - kCoarseLog2);            // p >> cshift < kCoarse
     static_assert(kCoarse <= kT && kCoarse % kWave == 0 && kCoarse <= kBins / 4, "coarse histogram geometry");
-    for (int i = tid; i < kCoarse; i += kT) sh.coarse[i] = 0;
-    zero_hist(sh);
-    if (tid == 0) { sh.maxbin = 0; sh.piv_bin = kBins - 1; sh.piv_before = n; }
-    __syncthreads();
+    // (order_prepare and a barrier behind it have cleared the histograms)
     uint64_t c[kCandPer];
     uint32_t place[kCandPer];
 #pragma unroll
@@ -288,21 +292,22 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();
-    // fine bins per coarse range, in proportion to its count (at least one where there is a candidate)
-    if (tid < kCoarse) {
-        const unsigned cnt = sh.coarse[tid];
+    // fine bins per coarse range, in proportion to its count (at least one where there is a candidate); one
+    // wave builds the table, kCoarse / 64 consecutive ranges per lane
+    if (wave == 0) {
+        constexpr int kPerLane = kCoarse / kWave;
         constexpr int kShared = kBins - kCoarse - kCoarse / 2;      // leaves room for the "at least one" and for rounding
-        const unsigned nf = cnt ? max(1u, (unsigned)((float)cnt * ((float)kShared / (float)n))) : 0u;
-        const unsigned incl = wave_scan_incl(nf);
-        if (lane == kWave - 1) sh.wtot[wave] = (int)incl;
-        sh.coarse[tid] = (nf << 16) | (incl - nf);                 // first fine bin within this wave's share, for now
-    }
-    __syncthreads();
-    if (tid < kCoarse) {
-        unsigned before = 0;
+        const float share = (float)kShared / (float)n;
+        unsigned nf[kPerLane], loc = 0;
 #pragma unroll
-        for (int w = 0; w < kCoarse / kWave; ++w) before += (w < wave) ? (unsigned)sh.wtot[w] : 0u;
-        sh.coarse[tid] += before;
+        for (int u = 0; u < kPerLane; ++u) {
+            const unsigned cnt = sh.coarse[lane * kPerLane + u];
+            nf[u] = cnt ? max(1u, (unsigned)((float)cnt * share)) : 0u;
+            loc += nf[u];
+        }
+        unsigned first = wave_scan_incl(loc) - loc;                 // first fine bin of this lane's ranges
+#pragma unroll
+        for (int u = 0; u < kPerLane; ++u) { sh.coarse[lane * kPerLane + u] = (nf[u] << 16) | first; first += nf[u]; }
     }
     __syncthreads();
     int meta[kCandPer];                      // (fine bin << 16) | arrival order within the bin; -1: no candidate
@@ -771,6 +776,8 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         if (!enough) continue;                   // optimistic threshold too high, or buffer full: stream again, safely
 
         // ---- end of row
+        if (n_held < 0) n_held = sh.cnt;
+        order_prepare(sh, n_held);               // (the barriers of the combine below stand behind it)
         {   // M = max over the threads; S = sum s * 2^(r - M*c), combined in fp64
             const float wm = wave_max(os.mx);
             if (lane == 0) sh.red[wave] = (double)wm;
@@ -785,14 +792,12 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             S = 0.0;
 #pragma unroll
             for (int w = 0; w < kW; ++w) S += sh.red[kW + w];
-            __syncthreads();
         }
         key_hi = short_key<BF16>(__float_as_uint(M));
         break;
     }
 
     // ---- exact cut to k, ordering and emission
-    if (n_held < 0) n_held = sh.cnt;
     const int n = min(n_held, k);
     const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi);
 
