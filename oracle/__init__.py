@@ -42,7 +42,7 @@ def lib() -> C.CDLL:
             build()
         _lib = C.CDLL(_LIB)
         for name in ("oracle_compress", "oracle_sample_draft", "oracle_verify",
-                     "oracle_sample_residual", "oracle_record_bytes"):
+                     "oracle_sample_residual", "oracle_resample_sparse", "oracle_record_bytes"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -172,6 +172,50 @@ def sample_residual(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarra
                                       _ptr(out.cdf_margin))
     if rc != 0:
         raise ValueError(f"oracle_sample_residual rc={rc}")
+    return out
+
+
+def rejected_rows(seq_off: np.ndarray, n_accept: np.ndarray) -> np.ndarray:
+    """Target row of sequence b at its first rejected (or bonus) position: seq_off[b] + b + n_accept[b]."""
+    seq_off = np.asarray(seq_off, np.int64)
+    B = seq_off.shape[0] - 1
+    return seq_off[:B] + np.arange(B, dtype=np.int64) + np.asarray(n_accept, np.int64)
+
+
+def compress_rejected(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray, n_accept: np.ndarray,
+                      k: int, top_p: float = 0.0) -> Compressed:
+    """The downlink record (Eq. 4): Top-K of the target distribution at each sequence's rejected position."""
+    rows = rejected_rows(seq_off, n_accept)
+    return compress(np.ascontiguousarray(tgt_logits[rows]), V, T, k, top_p)
+
+
+@dataclass
+class SparseResample:
+    out_tok: np.ndarray     # int32 [B]
+    resid_mass: np.ndarray  # float64 [B]
+    flags: np.ndarray       # uint32 [B]
+    cdf_margin: np.ndarray  # float64 [B]
+    weights: np.ndarray     # float64 [B,k]: the per-slot weights drawn from
+
+
+def resample_sparse(draft_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray, n_accept: np.ndarray,
+                    p: Compressed, uniforms: np.ndarray, renorm: int = 0) -> SparseResample:
+    dt = _logits(draft_logits)
+    _, ld = draft_logits.shape
+    seq_off = np.ascontiguousarray(seq_off, np.int32)
+    B = seq_off.shape[0] - 1
+    n_accept = np.ascontiguousarray(n_accept, np.int32)
+    u = np.ascontiguousarray(uniforms, np.float32)
+    out = SparseResample(np.empty(B, np.int32), np.empty(B, np.float64), np.zeros(B, np.uint32),
+                         np.empty(B, np.float64), np.zeros((B, p.k), np.float64))
+    rc = lib().oracle_resample_sparse(_ptr(draft_logits), C.c_int(dt), C.c_int64(ld), C.c_int32(V),
+                                      C.c_double(T), C.c_int32(B), _ptr(seq_off), _ptr(n_accept),
+                                      _ptr(p.idx), _ptr(p.prob), _ptr(p.count), _ptr(p.mass),
+                                      C.c_int32(p.k), C.c_int(renorm), _ptr(u),
+                                      _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
+                                      _ptr(out.cdf_margin), _ptr(out.weights))
+    if rc != 0:
+        raise ValueError(f"oracle_resample_sparse rc={rc}")
     return out
 
 

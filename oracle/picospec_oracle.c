@@ -12,7 +12,10 @@
  *   - Parallel verification with the acceptance test min(1, p/q) of standard
  *     speculative sampling: Section 3.3 (second paragraph) and the rule of
  *     Chen et al. cited in Section 2.1.
- *   - Correction token drawn from norm(max(0, P_j - Q_j)): Section 3.3.
+ *   - Correction token drawn from norm(max(0, P_j - Q_j)): Section 3.3; both
+ *     with the draft side compressed (dense target on the verifier) and, as the
+ *     paper ships it, with the target's Top-K record sent to the edge, which
+ *     resamples locally against its dense draft distribution.
  *   - Bonus token when every draft token is accepted: implied by Table 1's
  *     accepted lengths exceeding the draft length (Section 4.1 / 4.2).
  *
@@ -319,6 +322,83 @@ int oracle_sample_residual(const void *tgt_logits, int dtype, int64_t ld, int32_
         resid_mass[b] = (fl & ORACLE_FLAG_RESIDUAL_EMPTY) ? 0.0 : R;
         if (flags) flags[b] = fl;
         if (cdf_margin) cdf_margin[b] = fmin(fabs(target - prev), fabs(cum - target)) / R;
+        free(r);
+    }
+    return failed ? -2 : 0;
+}
+
+/*
+ * Edge-side local resampling on the sparse downlink (Section 3.3, last part: on a rejection at
+ * position j the cloud sends only the Top-K components of the target distribution, Eq. 4, and the
+ * edge draws the corrected token from norm(max(0, P_j - Q_j)) with its own, dense, Q_j).
+ * For sequence b: j = n_accept[b]; record b holds (id_s, prob_s), s < count[b], of target row
+ * seq_off[b]+b+j.  The edge knows the target only through the record: Pt(id_s) = prob_s
+ * (renorm 0, the values as sent) or prob_s/mass (renorm 1), Pt = 0 elsewhere, so the residual
+ * lives on the record's slots:
+ *     r_s = max(0, Pt(id_s) - Q_j(id_s)),   Q_j(x) = exp(z_d[x]/T - lse_d) of dense draft row seq_off[b]+j;
+ *     j = gamma_b (every draft token accepted): no Q, r_s = Pt(id_s) (the bonus token).
+ * R = sum r_s; token = id of the first slot, in slot order, whose inclusive cumulative r exceeds u*R,
+ * u = uniforms[seq_off[b]+b+gamma_b].  R <= 0: draw from Pt itself and flag it.
+ *   out_tok, resid_mass, flags [B]; cdf_margin [B] nullable (relative to the total weight);
+ *   weights [B,k] nullable: the r_s actually drawn from (0 in unused slots).
+ */
+int oracle_resample_sparse(const void *draft_logits, int dtype, int64_t ld, int32_t V, double T,
+                           int32_t B, const int32_t *seq_off, const int32_t *n_accept,
+                           const int32_t *p_idx, const double *p_prob, const int32_t *p_count,
+                           const double *p_mass, int32_t k, int renorm,
+                           const float *uniforms,
+                           int32_t *out_tok, double *resid_mass, uint32_t *flags,
+                           double *cdf_margin, double *weights)
+{
+    if (V < 1 || !(T > 0.0) || ld < V || B < 0 || k < 1) return -1;
+    const size_t esz = dtype == ORACLE_F32 ? 4 : 2;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t d0 = seq_off[b], gamma = seq_off[b + 1] - seq_off[b];
+        int32_t j = n_accept[b], c = p_count[b];
+        const int32_t *ids = p_idx + (size_t)b * k;
+        const double *pp = p_prob + (size_t)b * k;
+        double *r = (double *)malloc((size_t)k * sizeof *r);
+        if (!r) { failed = 1; continue; }
+        uint32_t fl = 0;
+        for (int32_t s = 0; s < c; ++s) r[s] = renorm ? pp[s] / p_mass[b] : pp[s]; /* Pt(id_s) */
+        if (j < gamma) {
+            const void *row = (const char *)draft_logits + (size_t)(d0 + j) * (size_t)ld * esz;
+            double l = row_lse(row, dtype, V, T);
+            for (int32_t s = 0; s < c; ++s) {
+                double q = exp(logit_at(row, dtype, ids[s]) / T - l);
+                double d = r[s] - q;
+                r[s] = d > 0.0 ? d : 0.0;
+            }
+        }
+        double R = 0.0;
+        for (int32_t s = 0; s < c; ++s) R += r[s];
+        if (!(R > 0.0)) { /* nothing of the record exceeds Q: draw from the record itself */
+            fl |= ORACLE_FLAG_RESIDUAL_EMPTY;
+            R = 0.0;
+            for (int32_t s = 0; s < c; ++s) { r[s] = renorm ? pp[s] / p_mass[b] : pp[s]; R += r[s]; }
+        }
+        double target = (double)uniforms[(int64_t)d0 + b + gamma] * R;
+        double cum = 0.0, prev = 0.0;
+        int32_t pick = -1;
+        for (int32_t s = 0; s < c; ++s) {
+            prev = cum;
+            cum += r[s];
+            if (cum > target) { pick = s; break; }
+        }
+        if (pick < 0) { /* rounding: last slot with weight */
+            pick = c - 1;
+            while (pick > 0 && !(r[pick] > 0.0)) --pick;
+            prev = cum;
+        }
+        out_tok[b] = c > 0 ? ids[pick] : -1;
+        resid_mass[b] = (fl & ORACLE_FLAG_RESIDUAL_EMPTY) ? 0.0 : R;
+        if (flags) flags[b] = fl;
+        if (cdf_margin) cdf_margin[b] = fmin(fabs(target - prev), fabs(cum - target)) / R;
+        if (weights) {
+            for (int32_t s = 0; s < k; ++s) weights[(size_t)b * k + s] = s < c ? r[s] : 0.0;
+        }
         free(r);
     }
     return failed ? -2 : 0;
