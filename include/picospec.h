@@ -8,6 +8,9 @@
  *   picospec_sample_draft    the drafter's token draw from that record (edge side, Section 3.3)
  *   picospec_verify          parallel verification: acceptance test, first rejection (Section 3.3)
  *   picospec_sample_residual correction token ~ norm(max(0, P_j - Q_j)), or the bonus token
+ *   picospec_row_stats / picospec_compress_rejected / picospec_resample_sparse
+ *                            the paper's own downlink: Top-K record of the target row at the
+ *                            rejected position, local resampling at the edge (Section 3.3, Eq. 4)
  *
  * Conventions shared by all calls
  *   - Every data pointer is a DEVICE pointer (HBM) unless marked "host".  The caller owns all
@@ -63,7 +66,8 @@ enum {
     PICOSPEC_FLAG_BAD_INPUT = 8u             /* token id outside [0,V), negative gamma_b, n_accept outside [0,gamma_b] */
 };
 
-enum { PICOSPEC_CALL_COMPRESS = 0, PICOSPEC_CALL_SAMPLE_DRAFT = 1, PICOSPEC_CALL_VERIFY = 2, PICOSPEC_CALL_SAMPLE_RESIDUAL = 3 };
+enum { PICOSPEC_CALL_COMPRESS = 0, PICOSPEC_CALL_SAMPLE_DRAFT = 1, PICOSPEC_CALL_VERIFY = 2, PICOSPEC_CALL_SAMPLE_RESIDUAL = 3,
+       PICOSPEC_CALL_COMPRESS_REJECTED = 4, PICOSPEC_CALL_RESAMPLE_SPARSE = 5 };
 enum { PICOSPEC_LIMIT_MAX_K = 0, PICOSPEC_LIMIT_MAX_V = 1 };
 
 /*
@@ -131,6 +135,58 @@ int picospec_sample_residual(const void* tgt_logits, int dtype, int64_t ld, int3
                              int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
                              const float* tgt_max, const float* tgt_sum,
                              const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                             int32_t k, int renorm, const float* uniforms,
+                             int32_t* out_tok, float* resid_mass, uint32_t* flags,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- The paper's own direction of the sparse record (Section 3.3, last part) -------------------
+ * The edge uplinks the scalars q_1..q_gamma (picospec_verify with q_scalar), the cloud verifies,
+ * and only on a rejection at position j it sends the Top-K record of the TARGET distribution P_j
+ * (Eq. 4); the edge then resamples locally from norm(max(0, P_j - Q_j)) with its own dense Q_j.
+ * The three calls below are that downlink; the calls above compress the draft side instead.
+ */
+
+/*
+ * Softmax statistics of n_rows rows (max, sum of exp((z - max)/T), log-sum-exp): what
+ * picospec_verify computes for the target rows, offered for the edge's dense draft rows.
+ *   row_max, row_sum [n_rows] out; row_lse [n_rows] out, may be NULL.
+ */
+int picospec_row_stats(const void* logits, int dtype, int64_t ld, int32_t n_rows, int32_t V, float temperature,
+                       float* row_max, float* row_sum, float* row_lse, void* stream);
+
+/*
+ * The downlink record (Eq. 4): picospec_compress of ONE target row per sequence, the row of its
+ * first rejected position (or of the bonus position when every draft token was accepted):
+ * target row seq_off[b] + b + n_accept[b], with n_accept[b] clamped to 0..gamma_b.
+ *   tgt_logits [n_draft + B, ld] in;  seq_off [B+1], n_accept [B] in
+ *   idx, prob [B,k], count, mass, lse [B] out (record b belongs to sequence b)
+ */
+int picospec_compress_rejected(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                               int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
+                               int32_t k, float top_p,
+                               int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Local resampling at the edge (Section 3.3: norm(max(0, P_j - Q_j))) from the downlink record.
+ * The target is known only through the record: Pt(id_s) = p_prob[s] (renorm 0, the values as
+ * sent) or p_prob[s] / p_mass (renorm 1), 0 elsewhere, so the residual lives on the record's slots:
+ *   r_s = max(0, Pt(id_s) - Q_j(id_s)),  Q_j(x) = exp((z_d[x] - draft_max) / T) / draft_sum of dense
+ *   draft row seq_off[b] + j, j = n_accept[b];  j = gamma_b: r_s = Pt(id_s) (bonus token).
+ * out_tok[b] = id of the first slot, in slot order, whose inclusive cumulative r exceeds u * R,
+ * R = sum r_s, u = uniforms[seq_off[b] + b + gamma_b]; resid_mass[b] = R.  R <= 0: the draw comes
+ * from Pt itself, resid_mass = 0, flag RESIDUAL_EMPTY.  An empty record gives out_tok = -1.
+ * With k < V this draw is biased against the exact residual by exactly the residual mass that
+ * lies off the record (total variation 1 - R_K / R for renorm 0); with k = V it is exact.
+ *   draft_logits [n_draft, ld] in; draft_max, draft_sum [n_draft] in (picospec_row_stats)
+ *   p_idx, p_prob [B,k], p_count, p_mass [B] in (picospec_compress_rejected); uniforms [n_draft + B] in
+ *   out_tok, resid_mass, flags [B] out (BAD_INPUT: n_accept outside 0..gamma_b, an id outside [0,V))
+ */
+int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                             int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
+                             const float* draft_max, const float* draft_sum,
+                             const int32_t* p_idx, const float* p_prob, const int32_t* p_count, const float* p_mass,
                              int32_t k, int renorm, const float* uniforms,
                              int32_t* out_tok, float* resid_mass, uint32_t* flags,
                              void* workspace, size_t workspace_bytes, void* stream);

@@ -22,6 +22,7 @@ CALL_COMPRESS, CALL_SAMPLE_DRAFT, CALL_VERIFY, CALL_SAMPLE_RESIDUAL = 0, 1, 2, 3
 LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
 
 EXPORTS = ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
+           "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_workspace_bytes", "picospec_limit", "picospec_strerror", "picospec_version")
 
 if not os.path.exists(LIB_PATH):
@@ -37,6 +38,11 @@ lib.picospec_verify.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p,
                                 _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_sample_residual.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
                                          _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_row_stats.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _p, _p, _p, _p]
+lib.picospec_compress_rejected.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _i32, _f,
+                                           _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_resample_sparse.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
+                                         _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_workspace_bytes.argtypes = [C.c_int, C.c_int, _i32, _i32, _i32]
 lib.picospec_workspace_bytes.restype = _sz
 lib.picospec_limit.argtypes = [C.c_int]
@@ -44,7 +50,7 @@ lib.picospec_limit.restype = _i64
 lib.picospec_strerror.argtypes = [C.c_int]
 lib.picospec_strerror.restype = C.c_char_p
 for _n in ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
-           "picospec_version"):
+           "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse", "picospec_version"):
     getattr(lib, _n).restype = C.c_int
 
 
@@ -176,6 +182,43 @@ def sample_residual(tgt_logits: torch.Tensor, V: int, temperature: float, seq_of
     _check(lib.picospec_sample_residual(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off), _ptr(na),
                                         _ptr(ver.tgt_max), _ptr(ver.tgt_sum),
                                         _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), q.k, renorm,
+                                        _ptr(uniforms), _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
+                                        None, 0, _stream()))
+    return out
+
+
+def row_stats(logits: torch.Tensor, V: int, temperature: float):
+    """picospec_row_stats -> (row_max, row_sum, row_lse), float32 [rows] each."""
+    dt, ld = _logits_2d(logits)
+    rows = logits.shape[0]
+    e = lambda: torch.empty(rows, dtype=torch.float32, device=logits.device)
+    mx, sm, ls = e(), e(), e()
+    _check(lib.picospec_row_stats(_ptr(logits), dt, ld, rows, V, temperature, _ptr(mx), _ptr(sm), _ptr(ls), _stream()))
+    return mx, sm, ls
+
+
+def compress_rejected(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+                      n_accept: torch.Tensor, k: int, top_p: float = 0.0, out: Compressed | None = None) -> Compressed:
+    """picospec_compress_rejected: the downlink record of every sequence's rejected (or bonus) target row."""
+    dt, ld = _logits_2d(tgt_logits)
+    B = seq_off.shape[0] - 1
+    out = out or alloc_compressed(B, k, tgt_logits.device)
+    _check(lib.picospec_compress_rejected(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off),
+                                          _ptr(n_accept), k, top_p, _ptr(out.idx), _ptr(out.prob), _ptr(out.count),
+                                          _ptr(out.mass), _ptr(out.lse), None, 0, _stream()))
+    return out
+
+
+def resample_sparse(draft_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+                    n_accept: torch.Tensor, draft_max: torch.Tensor, draft_sum: torch.Tensor, p: Compressed,
+                    uniforms: torch.Tensor, renorm: int = 0, out: Residual | None = None) -> Residual:
+    """picospec_resample_sparse: the edge's local draw from norm(max(0, P_j - Q_j)) on the record's slots."""
+    dt, ld = _logits_2d(draft_logits)
+    B = seq_off.shape[0] - 1
+    out = out or alloc_residual(B, draft_logits.device)
+    _check(lib.picospec_resample_sparse(_ptr(draft_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off),
+                                        _ptr(n_accept), _ptr(draft_max), _ptr(draft_sum),
+                                        _ptr(p.idx), _ptr(p.prob), _ptr(p.count), _ptr(p.mass), p.k, renorm,
                                         _ptr(uniforms), _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
                                         None, 0, _stream()))
     return out

@@ -47,7 +47,56 @@ int picospec_compress(const void* logits, int dtype, int64_t ld, int32_t n_rows,
     if (n_rows > 0 && (!idx || !prob || !count || !mass || !lse)) return PICOSPEC_EINVAL;
     if (int rc = check_workspace(PICOSPEC_CALL_COMPRESS, dtype, n_rows, V, k, workspace, workspace_bytes)) return rc;
     return hip_status(launch_compress(logits, dtype, ld, n_rows, V, temperature, k, top_p, idx, prob, count,
-                                      mass, lse, (hipStream_t)stream));
+                                      mass, lse, nullptr, nullptr, (hipStream_t)stream));
+}
+
+int picospec_row_stats(const void* logits, int dtype, int64_t ld, int32_t n_rows, int32_t V, float temperature,
+                       float* row_max, float* row_sum, float* row_lse, void* stream)
+{
+    if (int rc = check_logits(logits, dtype, ld, n_rows, V, temperature)) return rc;
+    if (n_rows > 0 && (!row_max || !row_sum)) return PICOSPEC_EINVAL;
+    return hip_status(launch_row_stats(logits, dtype, ld, n_rows, V, temperature, row_max, row_sum, row_lse,
+                                       (hipStream_t)stream));
+}
+
+int picospec_compress_rejected(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                               int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
+                               int32_t k, float top_p,
+                               int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
+    const int64_t rows = (int64_t)n_draft + B;
+    if (rows > INT32_MAX) return PICOSPEC_EINVAL;
+    if (int rc = check_logits(tgt_logits, dtype, ld, rows, V, temperature)) return rc;
+    if (k < 1 || k > V || std::isnan(top_p)) return PICOSPEC_EINVAL;
+    if (k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (B > 0 && (!seq_off || !n_accept || !idx || !prob || !count || !mass || !lse)) return PICOSPEC_EINVAL;
+    if (int rc = check_workspace(PICOSPEC_CALL_COMPRESS_REJECTED, dtype, B, V, k, workspace, workspace_bytes)) return rc;
+    return hip_status(launch_compress(tgt_logits, dtype, ld, B, V, temperature, k, top_p, idx, prob, count,
+                                      mass, lse, seq_off, n_accept, (hipStream_t)stream));
+}
+
+int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                             int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* n_accept,
+                             const float* draft_max, const float* draft_sum,
+                             const int32_t* p_idx, const float* p_prob, const int32_t* p_count, const float* p_mass,
+                             int32_t k, int renorm, const float* uniforms,
+                             int32_t* out_tok, float* resid_mass, uint32_t* flags,
+                             void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
+    if (int rc = check_logits(draft_logits, dtype, ld, n_draft, V, temperature)) return rc;
+    if (renorm != 0 && renorm != 1) return PICOSPEC_EINVAL;
+    if (k < 1) return PICOSPEC_EINVAL;
+    if (k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (B > 0 && (!seq_off || !n_accept || !p_idx || !p_prob || !p_count || !p_mass || !uniforms ||
+                  !out_tok || !resid_mass || !flags)) return PICOSPEC_EINVAL;
+    if (n_draft > 0 && (!draft_max || !draft_sum)) return PICOSPEC_EINVAL;
+    if (int rc = check_workspace(PICOSPEC_CALL_RESAMPLE_SPARSE, dtype, n_draft, V, k, workspace, workspace_bytes)) return rc;
+    return hip_status(launch_resample_sparse(draft_logits, dtype, ld, V, temperature, B, seq_off, n_accept,
+                                             draft_max, draft_sum, p_idx, p_prob, p_count, p_mass, k, renorm,
+                                             uniforms, out_tok, resid_mass, flags, (hipStream_t)stream));
 }
 
 int picospec_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,

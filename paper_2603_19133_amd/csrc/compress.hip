@@ -408,7 +408,8 @@ template <bool BF16>
 __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
-    float* __restrict__ mass, float* __restrict__ lse)
+    float* __restrict__ mass, float* __restrict__ lse,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
@@ -424,8 +425,15 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     constexpr int RING = PICOSPEC_COMPRESS_RING * (2 / SV);  // sub-tile buffers: one in use, the others in flight
     static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int64_t row = blockIdx.x;
-    const RowView rv = row_view<BF16>(logits, ld, row, V);
+    const int64_t row = blockIdx.x;              // row of the record written
+    // Row read: the same one, or (downlink record, Section 3.3) the target row of sequence `row` at its
+    // first rejected or bonus position, seq_off[b] + b + n_accept[b] (n_accept clamped to 0..gamma_b).
+    int64_t in_row = row;
+    if (seq_off) {
+        const int d0 = seq_off[row], g = max(seq_off[row + 1] - d0, 0);
+        in_row = (int64_t)d0 + row + min(max(n_accept[row], 0), g);
+    }
+    const RowView rv = row_view<BF16>(logits, ld, in_row, V);
     const int n_sub = (rv.L + SUB - 1) / SUB;
     const int nq = (rv.L + N - 1) / N;           // 16-byte vectors that overlap the row
     const float c = 1.4426950408889634f * inv_T;
@@ -933,7 +941,7 @@ __global__ __launch_bounds__(256) void sample_draft_kernel(
 
 hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
-                           float* lse, hipStream_t stream)
+                           float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream)
 {
     static bool attr_set[2] = {false, false};
     const size_t smem = sizeof(CompressShared);
@@ -948,8 +956,8 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
     }
     if (n_rows == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
-    if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse);
-    else       hipLaunchKernelGGL(f32, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse);
+    if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept);
+    else       hipLaunchKernelGGL(f32, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept);
     return hipGetLastError();
 }
 

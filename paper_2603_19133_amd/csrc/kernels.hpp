@@ -10,9 +10,11 @@ namespace picospec {
 constexpr int kMaxK = 4096;          // candidate buffer in LDS holds 16384 entries; k beyond this is refused
 constexpr int kMaxV = 1 << 20;       // residual sampler keeps one partial sum per 256/512-element segment in LDS
 
+// seq_off / n_accept: both null (record r from row r), or the downlink's row map (record b from target
+// row seq_off[b] + b + n_accept[b])
 hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
-                           float* lse, hipStream_t stream);
+                           float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream);
 
 hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
                                int k, int n_rows, const float* uniforms, int32_t* tok, float* q_scalar,
@@ -34,5 +36,12 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                            int k, int renorm, const float* uniforms,
                            int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
+
+hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t ld, int V, float temperature,
+                                  int B, const int32_t* seq_off, const int32_t* n_accept,
+                                  const float* draft_max, const float* draft_sum,
+                                  const int32_t* p_idx, const float* p_prob, const int32_t* p_count, const float* p_mass,
+                                  int k, int renorm, const float* uniforms,
+                                  int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
 
 }  // namespace picospec
