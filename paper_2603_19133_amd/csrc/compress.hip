@@ -409,7 +409,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
     float* __restrict__ mass, float* __restrict__ lse,
-    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept)
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept, int ahead)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
@@ -805,6 +805,21 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         break;
     }
 
+    // ---- While this row is ordered and emitted, the first sub-tiles of the row that will take a slot like
+    //      this one next (`ahead` rows further: as many rows as the chip holds at a time, same XCD) are pulled
+    //      into the caches with ordinary loads whose data is dropped, so that row does not start by waiting
+    //      for HBM.  One register quadruple takes all of them (tied operand: loads return in order).
+    u32x4_t dropped = {0u, 0u, 0u, 0u};
+    if (ahead > 0 && row + ahead < (int64_t)gridDim.x) {
+        const RowView nv = row_view<BF16>(logits, ld, row + ahead, V);
+        const int nq2 = (nv.L + N - 1) / N;
+#pragma unroll
+        for (int j = 0; j < RING * SV; ++j) {
+            const uint4* p = nv.base + min(j * kT + tid, nq2 - 1);
+            asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(dropped) : "v"(p));
+        }
+    }
+
     // ---- exact cut to k, ordering and emission
     const int n = min(n_held, k);
     const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi);
@@ -893,6 +908,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         count[row] = (int)tc;
         lse[row] = (float)((double)M * (double)inv_T + log(S));
     }
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(dropped));   // the dropped loads have landed before the wave ends
 }
 
 // The drafter's draw: inverse CDF over the used slots, one wave per row.
@@ -955,9 +971,22 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
         attr_set[which] = true;
     }
     if (n_rows == 0) return hipSuccess;
+    // rows resident at a time = 2 workgroups per CU: the distance of the look-ahead loads (none with a row map)
+    static int resident[16] = {0};
+    int ahead = 0;
+    if (!seq_off) {
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16) {
+            if (resident[dev] == 0) {
+                int cus = 0;
+                resident[dev] = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? 2 * cus : -1;
+            }
+            ahead = resident[dev] > 0 ? resident[dev] : 0;
+        }
+    }
     const float inv_T = 1.0f / temperature;
-    if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept);
-    else       hipLaunchKernelGGL(f32, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept);
+    if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
+    else       hipLaunchKernelGGL(f32, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
     return hipGetLastError();
 }
 
