@@ -2,21 +2,23 @@
 // softmax statistics: one workgroup of 512 threads per row, two workgroups per CU, one HBM pass
 // per row.
 //
-// Streaming selection.  A row is read in sub-tiles of two 16-byte vectors per thread through a ring
-// of four register buffers (three sub-tiles in flight behind the one being processed).
+// Streaming selection.  A row is read with buffer loads (descriptor base + scalar offset + one
+// constant per-lane offset) in sub-tiles of two 16-byte vectors per thread through a ring of four
+// register buffers (three sub-tiles in flight behind the one being processed).
 //   * The first 8192 elements (the sample) stay in registers while a two-pass radix histogram over
 //     their order-preserving logit keys finds a threshold: a value with at least r of the sample's
 //     elements at or above it.
 //   * Optimistic pass: r is chosen so that about k + 4.5 sqrt(k) + 20 elements of the whole row are
 //     expected at or above the threshold (for exchangeable rows).  Every element of the row at
-//     or above it -- tile 0 included -- is appended to a candidate buffer in LDS (value, id).
-//     If the row ends with at least k candidates, the exact top k is among them, because nothing
-//     at or above the threshold was dropped.  Waves run free in this pass; a reservation that
-//     does not fit the buffer, or fewer than k candidates at the end, gives the pass up.
+//     or above it -- the sample included -- claims a slot of the candidate buffer in LDS with an
+//     atomic of its own and writes (value, id) there; the softmax arithmetic sits between claim and
+//     write.  If the row ends with at least k candidates that fit the buffer, the exact top k is
+//     among them, because nothing at or above the threshold was dropped.  Waves run free in this
+//     pass; too many or too few candidates give the pass up.
 //   * Safe pass (only after a failed optimistic pass, or when the optimistic rank would not pay):
-//     r = k, so the threshold is at or below the k-th largest of tile 0.  The waves meet after
-//     every tile; when the buffer is full it is pruned to the exact top k of everything seen, and
-//     from then on an element must be strictly larger than the k-th (rows are streamed in
+//     r = k, so the threshold is at or below the k-th largest of the sample.  The waves meet after
+//     every sub-tile; when the buffer is full it is pruned to the exact top k of everything seen,
+//     and from then on an element must be strictly larger than the k-th (rows are streamed in
 //     ascending id, so equal logits that come later lose the tie).
 //   * The candidates are cut to exactly k and ordered in one step by a histogram rank sort on the
 //     composite
@@ -68,7 +70,7 @@ struct __align__(16) CompressShared {
     int n_holes, n_fills;                   // compaction of a prune
     int piv_bin, piv_before, piv_count;     // radix-select broadcast
     int maxbin;
-    int overflowed;                         // optimistic pass: a reservation did not fit
+    int overflowed;                         // a reservation of the sample did not fit (cannot happen: kept as a guard)
     int epoch_overflow[3];                  // safe pass, per attempt epoch: some wave did not fit
     int epoch_valid[3];                     // safe pass, per attempt epoch: first reservation that did not fit
 };
@@ -497,12 +499,12 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         os.s += acc;
         return bm;
     };
-    // Appending the elements that pass (v > tau, or with ALL every element that is not NaN) takes two
-    // steps so that independent work can sit between them and hide the LDS atomic's latency:
-    // reserve_vecs counts the wave's candidates (one ballot per element column) and reserves their
-    // slots with one LDS atomic; place_vecs forms the lane masks again (sixteen of them would not fit
-    // the scalar file) and writes (value, id).  x0 = id of this thread's first element; vector jj
-    // starts kT*N ids after vector jj-1.
+    // Safe pass: appending the elements that pass (v > tau, or with ALL every element that is not NaN)
+    // by wave-wide reservation, so that a reservation that does not fit writes nothing and can be
+    // repeated after a prune.  reserve_vecs counts the wave's candidates (one ballot per element
+    // column) and reserves their slots with one LDS atomic; place_vecs forms the lane masks again and
+    // writes (value, id).  x0 = id of this thread's first element; vector jj starts kT*N ids after
+    // vector jj-1.
     struct Reservation { int total, base; };   // base is valid in lane 0 until place_vecs broadcasts it
     auto reserve_vecs = [&](auto nvv_tag, auto all_tag, const float* v, float tau) {
         constexpr int NVV = decltype(nvv_tag)::value;
