@@ -578,7 +578,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                          "s_mov_b64 exec, %[sv]"
                          : [slot] "=&v"(slot[e]), [m] "=&s"(passed[e]), [sv] "=&s"(saved)
                          : [x] "v"(v[e]), [t] "v"(tau), [ca] "v"(ca), [four] "v"(four)
-                         : "memory");
+                         : "memory", "scc");
         }
     };
     auto put_asm = [&, wrap](auto nvv_tag, const float* v, int* slot, const unsigned long long* passed, int x0) {
@@ -612,7 +612,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                              : [sv] "=&s"(saved), [at] "=&v"(at), [id] "=&v"(id)
                              : [m] "s"(passed[j * N + e]), [slot] "v"(slot[j * N + e]), [wrap] "v"(wrap), [va] "s"(va),
                                [c] "s"(j * kT * N + e), [x0] "v"(x0), [x] "v"(v[j * N + e])
-                             : "memory");
+                             : "memory", "scc");
             }
     };
     static_assert(offsetof(CompressShared, cand_id) - offsetof(CompressShared, cand_val) == 128 * 64 * 4,

@@ -128,3 +128,63 @@ def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     spec = importlib.util.spec_from_file_location("binding_copy", dst)
     with pytest.raises(ImportError, match="no CPU fallback"):
         spec.loader.exec_module(importlib.util.module_from_spec(spec))
+
+
+def test_downlink_calls_reject_misuse(B):
+    """Host-visible misuse of the downlink calls returns an error code before any launch (no GPU needed)."""
+    lib = B.lib
+    f32 = 0
+    # row statistics: null outputs, bad temperature
+    assert lib.picospec_row_stats(FAKE, f32, 100, 2, 100, 1.0, None, FAKE, None, None) == B.EINVAL
+    assert lib.picospec_row_stats(FAKE, f32, 100, 2, 100, 0.0, FAKE, FAKE, None, None) == B.EINVAL
+    assert lib.picospec_row_stats(FAKE, 7, 100, 2, 100, 1.0, FAKE, FAKE, None, None) == B.EDTYPE
+    # record of the rejected rows: k out of range, missing row map, k beyond the limit
+    ok = dict(tgt=FAKE, dt=f32, ld=50, V=50, T=1.0, Bn=2, N=6, seq=FAKE, na=FAKE, k=8, tp=0.0, outs=(FAKE,) * 5)
+
+    def rej(**kw):
+        a = dict(ok, **kw)
+        return lib.picospec_compress_rejected(a["tgt"], a["dt"], a["ld"], a["V"], a["T"], a["Bn"], a["N"], a["seq"], a["na"],
+                                              a["k"], a["tp"], *a["outs"], None, 0, None)
+
+    assert rej(k=0) == B.EINVAL and rej(k=51) == B.EINVAL and rej(seq=None) == B.EINVAL and rej(na=None) == B.EINVAL
+    assert rej(outs=(FAKE, None, FAKE, FAKE, FAKE)) == B.EINVAL and rej(Bn=-1) == B.EINVAL
+    assert rej(V=10000, ld=10000, k=5000) == B.EUNSUPPORTED
+    # local resampling: renorm flag, null record, missing draft statistics
+    okr = dict(d=FAKE, dt=f32, ld=50, V=50, T=1.0, Bn=2, N=6, seq=FAKE, na=FAKE, st=(FAKE, FAKE), rec=(FAKE,) * 4, k=8,
+               rn=0, u=FAKE, outs=(FAKE,) * 3)
+
+    def res(**kw):
+        a = dict(okr, **kw)
+        return lib.picospec_resample_sparse(a["d"], a["dt"], a["ld"], a["V"], a["T"], a["Bn"], a["N"], a["seq"], a["na"],
+                                            *a["st"], *a["rec"], a["k"], a["rn"], a["u"], *a["outs"], None, 0, None)
+
+    assert res(rn=2) == B.EINVAL and res(rec=(FAKE, None, FAKE, FAKE)) == B.EINVAL and res(st=(None, FAKE)) == B.EINVAL
+    assert res(k=0) == B.EINVAL and res(k=5000) == B.EUNSUPPORTED and res(u=None) == B.EINVAL
+    assert res(outs=(None, FAKE, FAKE)) == B.EINVAL and res(T=float("nan")) == B.EINVAL
+
+
+def test_compress_kernels_keep_everything_in_registers():
+    """The compress kernel issues LDS atomics and loads by hand and reads their results later; a register
+    spilled in between would carry a stale value.  The build must therefore report no vector-register
+    spill for either instantiation (cross-compiled here, no GPU needed)."""
+    import subprocess
+    from paper_2603_19133_amd import build as bld
+    if not os.path.exists(bld.HIPCC):
+        pytest.skip("hipcc not found")
+    src = os.path.join(bld.CSRC, "compress.hip")
+    flags = [f for f in bld.FLAGS if f not in ("-shared", "-fPIC")]
+    out = subprocess.run([bld.HIPCC, *flags, "-c", "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+                          "-o", os.devnull, src], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-2000:]
+    spills = {}
+    name = None
+    for line in out.stderr.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"VGPRs Spill: (\d+)", line)
+        if m and name:
+            spills[name] = int(m.group(1))
+    kernels = {k: v for k, v in spills.items() if "compress_kernel" in k}
+    assert len(kernels) == 2, spills
+    assert all(v == 0 for v in kernels.values()), kernels
