@@ -656,7 +656,37 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
 #pragma unroll
             for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); }
             const int target = optimistic ? r_opt : k;
-            if (more && n0 > target && key_hi > key_lo) {
+            bool have_tau = false;
+            if (optimistic && more && n0 > target) {
+                // Optimistic pass: the threshold only has to be about right (the count at the end of the row
+                // decides), so one histogram pass over a linear scale of the sample's value range does: bin
+                // 0 holds the largest values.  A crowded pivot bin (a value range stretched by outliers)
+                // leaves the job to the exact radix passes below.
+                const float vmax = __uint_as_float(bits_of_short_key<BF16>(key_hi));
+                const float vmin = __uint_as_float(bits_of_short_key<BF16>(key_lo));
+                if (vmax > vmin && vmin > kNegInf && vmax < __builtin_huge_valf()) {
+                    const float width = (vmax - vmin) * (1.0f / (float)kBins);
+                    const float scale = 1.0f / width;
+                    zero_hist(sh);
+                    __syncthreads();
+#pragma unroll
+                    for (int e = 0; e < E0; ++e)
+                        if (v[e] == v[e]) atomicAdd(&sh.hist[min((int)((vmax - v[e]) * scale), kBins - 1)], 1u);
+                    __syncthreads();
+                    find_pivot_bin(sh, target);
+                    if (scale < __builtin_huge_valf() && sh.piv_count <= max(8, target / 4)) {
+                        const float t = vmax - ((float)(sh.piv_bin + 1) + 0.01f) * width;   // below every element of the bins up to the pivot
+                        if (t > kNegInf) {
+                            tau = float_below(t);
+                            admit_all = false;
+                            have_tau = true;
+                            key_lo = short_key<BF16>(__float_as_uint(tau));
+                        }
+                    }
+                    __syncthreads();             // (the histogram and the pivot words are reused below)
+                }
+            }
+            if (!have_tau && more && n0 > target && key_hi > key_lo) {
                 // two histogram passes over the keys in registers: a key with >= target elements of the sample at or above it
                 uint32_t lo = key_lo;
                 const uint32_t range = key_hi - key_lo;
