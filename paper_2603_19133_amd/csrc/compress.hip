@@ -832,6 +832,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             S = 0.0;
 #pragma unroll
             for (int w = 0; w < kW; ++w) S += sh.red[kW + w];
+            if (tid == kT - 1) lse[row] = (float)((double)M * (double)inv_T + log(S));   // (off the last wave's critical path later on)
         }
         key_hi = short_key<BF16>(__float_as_uint(M));
         break;
@@ -855,6 +856,10 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     // ---- exact cut to k, ordering and emission
     const int n = min(n_held, k);
     const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi);
+
+    // the dropped loads have landed (they were issued a whole ordering ago); waiting here, in front of the
+    // record's stores, keeps the wave from waiting for those at its end
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(dropped));
 
     const double cd = 1.4426950408889634 * (double)inv_T;
     const double invS = 1.0 / S;
@@ -938,9 +943,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         for (int w = 0; w < kW; ++w) { tm += sh.red[w]; tc += sh.red[kW + w]; }
         mass[row] = (float)tm;
         count[row] = (int)tc;
-        lse[row] = (float)((double)M * (double)inv_T + log(S));
     }
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(dropped));   // the dropped loads have landed before the wave ends
 }
 
 // The drafter's draw: inverse CDF over the used slots, one wave per row.
