@@ -13,18 +13,71 @@ constexpr int kWaves = kThreads / kWave;
 constexpr float kNegInf = -__builtin_huge_valf();
 
 // ---------------------------------------------------------------- wave64 / workgroup reductions
+//
+// Cross-lane steps inside a row of 16 lanes use DPP operand modifiers (no trip through the LDS
+// crossbar); the four rows of a wave are combined through scalar registers (v_readlane).
 
-template <typename T>
-__device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+constexpr int kDppQuadXor1 = 0xB1;        // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;        // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7 - i within each half row
+constexpr int kDppRowMirror = 0x140;      // lane i <-> 15 - i within each row
+constexpr int kDppRowShr = 0x110;         // + n: lane i reads lane i - n of its row (0 where there is none)
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_word(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
+
+template <int CTRL, typename T>
+__device__ __forceinline__ T dpp(T v) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit lanes");
+    if constexpr (sizeof(T) == 4) {
+        int w;
+        __builtin_memcpy(&w, &v, 4);
+        w = dpp_word<CTRL>(w);
+        __builtin_memcpy(&v, &w, 4);
+    } else {
+        int w[2];
+        __builtin_memcpy(w, &v, 8);
+        w[0] = dpp_word<CTRL>(w[0]);
+        w[1] = dpp_word<CTRL>(w[1]);
+        __builtin_memcpy(&v, w, 8);
+    }
     return v;
 }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+// value of `v` in lane `lane` (a constant), in every lane
+template <typename T>
+__device__ __forceinline__ T read_lane(T v, int lane) {
+    if constexpr (sizeof(T) == 4) {
+        int w;
+        __builtin_memcpy(&w, &v, 4);
+        w = __builtin_amdgcn_readlane(w, lane);
+        __builtin_memcpy(&v, &w, 4);
+    } else {
+        int w[2];
+        __builtin_memcpy(w, &v, 8);
+        w[0] = __builtin_amdgcn_readlane(w[0], lane);
+        w[1] = __builtin_amdgcn_readlane(w[1], lane);
+        __builtin_memcpy(&v, w, 8);
+    }
     return v;
+}
+
+// sum over the 64 lanes, in every lane (the same bits in every lane: each step adds a pair both ways)
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+    v += dpp<kDppQuadXor1>(v);
+    v += dpp<kDppQuadXor2>(v);
+    v += dpp<kDppRowHalfMirror>(v);
+    v += dpp<kDppRowMirror>(v);
+    return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp<kDppQuadXor1>(v));
+    v = fmaxf(v, dpp<kDppQuadXor2>(v));
+    v = fmaxf(v, dpp<kDppRowHalfMirror>(v));
+    v = fmaxf(v, dpp<kDppRowMirror>(v));
+    return fmaxf(fmaxf(read_lane(v, 0), read_lane(v, 16)), fmaxf(read_lane(v, 32), read_lane(v, 48)));
 }
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
@@ -44,16 +97,21 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
     return v;
 }
 
-// inclusive prefix sum across the 64 lanes of a wave
+// inclusive prefix sum across the 64 lanes of a wave: four shift-and-add steps inside each row, then
+// the totals of the rows in front
 template <typename T>
 __device__ __forceinline__ T wave_scan_incl(T v) {
     const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        T w = __shfl_up(v, o, kWave);
-        if (lane >= o) v += w;
-    }
-    return v;
+    v += dpp<kDppRowShr + 1>(v);
+    v += dpp<kDppRowShr + 2>(v);
+    v += dpp<kDppRowShr + 4>(v);
+    v += dpp<kDppRowShr + 8>(v);
+    const T r0 = read_lane(v, 15), r1 = read_lane(v, 31), r2 = read_lane(v, 47);
+    T before = T(0);
+    if (lane >= 16) before += r0;
+    if (lane >= 32) before += r1;
+    if (lane >= 48) before += r2;
+    return v + before;
 }
 
 // ---------------------------------------------------------------- order-preserving keys
