@@ -121,6 +121,25 @@ def test_compress_unaligned_rows(gpu, pu, ps, shift, dtype):
     pu.compare_compress(g2, o2)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_more_rows_than_resident_workgroups(gpu, pu, ps, dtype):
+    """More rows than the chip holds at a time (the look-ahead loads of the next generation of rows are
+    live), odd leading dimension so that most rows start off a 16-byte boundary, and a row count that is
+    not a multiple of anything; also the same through the row statistics."""
+    _announce("compress many rows", dtype)
+    rows, V, ld, k = 1237, 9001, 9003, 70
+    rng = np.random.default_rng(12)
+    full = (rng.standard_normal((rows, ld)) * 3).astype(np.float32)
+    stored = full if dtype == "f32" else W.to_bf16_bits(full)
+    o = oracle.compress(stored, V, 0.8, k)
+    dev = pu.to_device(stored, gpu)
+    g = ps.compress(dev, V, 0.8, k)
+    mx, sm, ls = ps.row_stats(dev, V, 0.8)
+    torch.cuda.synchronize()
+    pu.compare_compress(g, o)
+    pu.assert_close(pu.n(ls), o.lse, pu.RTOL_LSE, "row_stats lse", atol=2e-6)
+
+
 @pytest.mark.parametrize("tau,k", [(0.5, 512), (0.9, 2048), (0.95, 64), (0.999, 4096)])
 def test_compress_top_p(gpu, pu, ps, tau, k):
     _announce("compress top-p", tau, k)
