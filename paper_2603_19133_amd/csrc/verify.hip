@@ -8,14 +8,15 @@ namespace picospec {
 
 namespace {
 
-// One workgroup per row: M = max z, S = sum exp((z - M)/T), lse = M/T + ln S.
-template <bool BF16, int NV>
-__global__ __launch_bounds__(kThreads) void row_stats_kernel(
+// One workgroup of THREADS threads per row, NV 16-byte vectors per thread and trip: M = max z, S = sum exp((z - M)/T), lse = M/T + ln S.
+template <bool BF16, int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void row_stats_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T,
     float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse)
 {
-    __shared__ double red[2 * kWaves];
-    constexpr int N = Vec<BF16>::N, E = NV * N, TILE = kThreads * E;
+    __shared__ double red[2 * (THREADS / kWave)];
+    constexpr int N = Vec<BF16>::N, E = NV * N, TILE = THREADS * E;
+    static_assert(E <= 32, "one bit of the validity mask per element");
     const int tid = threadIdx.x;
     const int64_t row = blockIdx.x;
     const RowView rv = row_view<BF16>(logits, ld, row, V);
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
     auto load_tile = [&](int it, uint4 (&dst)[NV]) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
-            int q = it * (kThreads * NV) + j * kThreads + tid;
+            int q = it * (THREADS * NV) + j * THREADS + tid;
             dst[j] = make_uint4(0, 0, 0, 0);
             if (vec_in_row<BF16>(rv, q)) dst[j] = load16_stream(rv.base + q);
         }
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
         if (it == 0 || it == n_tiles - 1) {
             unsigned vm = 0;
 #pragma unroll
-            for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * (kThreads * NV) + j * kThreads + tid) << (j * N);
+            for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * (THREADS * NV) + j * THREADS + tid) << (j * N);
 #pragma unroll
             for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : kNegInf;
         }
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
         for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
     }
     float M; double S;
-    block_softmax_stats(os.m, os.s, c, red, M, S);
+    block_softmax_stats<THREADS / kWave>(os.m, os.s, c, red, M, S);
     if (tid == 0) {
         row_max[row] = M;
         row_sum[row] = (float)S;
@@ -187,8 +188,16 @@ hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_row
 {
     if (n_rows == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
-    if (dtype == 1) hipLaunchKernelGGL((row_stats_kernel<true, 4>), dim3(n_rows), dim3(kThreads), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse);
-    else            hipLaunchKernelGGL((row_stats_kernel<false, 4>), dim3(n_rows), dim3(kThreads), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse);
+    // fp32 rows are HBM-bound with any shape.  bf16 rows carry twice the arithmetic per byte: small
+    // workgroups (many per CU, out of step, short ragged tails) keep the vector ALUs busier, as long as
+    // there are enough rows to fill the chip with them.
+#define PICOSPEC_ROW_STATS(BF, NVV, TH) \
+    hipLaunchKernelGGL((row_stats_kernel<BF, NVV, TH>), dim3(n_rows), dim3(TH), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse)
+    if (dtype != 1)           PICOSPEC_ROW_STATS(false, 4, kThreads);
+    else if (n_rows >= 2048)  PICOSPEC_ROW_STATS(true, 4, 256);
+    else if (n_rows >= 1024)  PICOSPEC_ROW_STATS(true, 2, 512);
+    else                      PICOSPEC_ROW_STATS(true, 2, kThreads);
+#undef PICOSPEC_ROW_STATS
     return hipGetLastError();
 }
 

@@ -140,6 +140,26 @@ def test_compress_more_rows_than_resident_workgroups(gpu, pu, ps, dtype):
     pu.assert_close(pu.n(ls), o.lse, pu.RTOL_LSE, "row_stats lse", atol=2e-6)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows", [700, 1237, 2300])
+def test_row_stats_launch_shapes(gpu, pu, ps, dtype, rows):
+    """The row statistics pick their workgroup size from the row count and the dtype: every shape gives
+    the oracle's max, sum and lse (rows off the 16-byte boundary, ragged tails, a few -inf entries)."""
+    _announce("row_stats shapes", dtype, rows)
+    V, ld, T = 5003, 5005, 0.9
+    rng = np.random.default_rng(rows)
+    full = (rng.standard_normal((rows, ld)) * 4).astype(np.float32)
+    full[::7, 11] = -np.inf
+    stored = full if dtype == "f32" else W.to_bf16_bits(full)
+    o = oracle.compress(stored, V, T, 1)
+    mx, sm, ls = ps.row_stats(pu.to_device(stored, gpu), V, T)
+    torch.cuda.synchronize()
+    z = (stored if dtype == "f32" else W.bf16_bits_to_f32(stored)).astype(np.float64)[:, :V]
+    assert np.array_equal(pu.n(mx).astype(np.float64), z.max(axis=1))
+    pu.assert_close(pu.n(ls), o.lse, pu.RTOL_LSE, "row_stats lse", atol=2e-6)
+    pu.assert_close(pu.n(sm), np.exp(o.lse - z.max(axis=1) / T), 1e-5, "row_stats sum")
+
+
 @pytest.mark.parametrize("tau,k", [(0.5, 512), (0.9, 2048), (0.95, 64), (0.999, 4096)])
 def test_compress_top_p(gpu, pu, ps, tau, k):
     _announce("compress top-p", tau, k)
