@@ -994,30 +994,25 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
                            float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream)
 {
-    static bool attr_set[2] = {false, false};
+    static bool limit_raised[2][kMaxDevices] = {};
+    static int resident[kMaxDevices] = {};       // rows resident at a time (2 workgroups per CU): the distance of the look-ahead loads
     const size_t smem = sizeof(CompressShared);
     auto f32 = compress_kernel<false>;
     auto b16 = compress_kernel<true>;
     const int which = dtype == 1;
-    if (!attr_set[which]) {
-        hipError_t e = hipFuncSetAttribute(which ? (const void*)b16 : (const void*)f32,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    int dev = 0;
+    {
+        hipError_t e = raise_lds_limit_once(which ? (const void*)b16 : (const void*)f32, smem, limit_raised[which], dev);
         if (e != hipSuccess) return e;
-        attr_set[which] = true;
     }
     if (n_rows == 0) return hipSuccess;
-    // rows resident at a time = 2 workgroups per CU: the distance of the look-ahead loads (none with a row map)
-    static int resident[16] = {0};
     int ahead = 0;
-    if (!seq_off) {
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16) {
-            if (resident[dev] == 0) {
-                int cus = 0;
-                resident[dev] = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? 2 * cus : -1;
-            }
-            ahead = resident[dev] > 0 ? resident[dev] : 0;
+    if (!seq_off) {                              // (no look-ahead with a row map: the next row is not known from the row number)
+        if (resident[dev] == 0) {
+            int cus = 0;
+            resident[dev] = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? 2 * cus : -1;
         }
+        ahead = resident[dev] > 0 ? resident[dev] : 0;
     }
     const float inv_T = 1.0f / temperature;
     if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);

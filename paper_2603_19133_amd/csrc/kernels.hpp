@@ -10,6 +10,21 @@ namespace picospec {
 constexpr int kMaxK = 4096;          // candidate buffer in LDS holds 16384 entries; k beyond this is refused
 constexpr int kMaxV = 1 << 20;       // residual sampler keeps one partial sum per 256/512-element segment in LDS
 
+// Kernels whose dynamic LDS exceeds the 64 KB default need their limit raised once per device and kernel.
+// `done` is the caller's per-device record for that kernel; the current device's ordinal comes back in `dev`.
+constexpr int kMaxDevices = 64;
+inline hipError_t raise_lds_limit_once(const void* kernel, size_t bytes, bool (&done)[kMaxDevices], int& dev) {
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!done[dev]) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        done[dev] = true;
+    }
+    return hipSuccess;
+}
+
 // seq_off / n_accept: both null (record r from row r), or the downlink's row map (record b from target
 // row seq_off[b] + b + n_accept[b])
 hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,

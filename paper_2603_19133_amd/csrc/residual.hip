@@ -291,16 +291,15 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            int k, int renorm, const float* uniforms,
                            int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream)
 {
-    static bool attr_set[2] = {false, false};
+    static bool limit_raised[2][kMaxDevices] = {};
     const size_t smem = sizeof(ResidualShared);
     auto f32 = residual_kernel<false>;
     auto b16 = residual_kernel<true>;
     const int which = dtype == 1;
-    if (!attr_set[which]) {
-        hipError_t e = hipFuncSetAttribute(which ? (const void*)b16 : (const void*)f32,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    {
+        int dev = 0;
+        hipError_t e = raise_lds_limit_once(which ? (const void*)b16 : (const void*)f32, smem, limit_raised[which], dev);
         if (e != hipSuccess) return e;
-        attr_set[which] = true;
     }
     if (B == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
