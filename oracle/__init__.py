@@ -4,8 +4,8 @@ TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()`` an
 ``cpu_baseline`` leg of ``bench.py``.  Nothing in the product package imports this, and this
 package imports nothing from the product package.
 
-The arithmetic lives in ``picospec_oracle.c`` (plain C, fp64); this module only builds it with gcc
-and marshals numpy arrays into it.
+The arithmetic lives in ``picospec_oracle.c`` (plain C, fp64) and the wire formats in
+``picospec_wire_oracle.c``; this module only builds them with gcc and marshals numpy arrays into them.
 """
 from __future__ import annotations
 
@@ -18,6 +18,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "picospec_oracle.c")
+_SRC_WIRE = os.path.join(_HERE, "picospec_wire_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 F32, BF16 = 0, 1
@@ -27,7 +28,7 @@ FLAG_TOKEN_NOT_IN_SUPPORT, FLAG_NONFINITE, FLAG_RESIDUAL_EMPTY = 1, 2, 4
 def build() -> str:
     """Compile the C oracle (no fast-math, so libm exp/log and IEEE ordering are kept)."""
     cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-           "-o", _LIB, _SRC, "-lm"]
+           "-o", _LIB, _SRC, _SRC_WIRE, "-lm"]
     subprocess.run(cmd, check=True)
     return _LIB
 
@@ -38,11 +39,13 @@ _lib = None
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_WIRE)):
             build()
         _lib = C.CDLL(_LIB)
         for name in ("oracle_compress", "oracle_sample_draft", "oracle_verify",
-                     "oracle_sample_residual", "oracle_resample_sparse", "oracle_record_bytes"):
+                     "oracle_sample_residual", "oracle_resample_sparse", "oracle_record_bytes",
+                     "oracle_wire_quantise", "oracle_pack_downlink", "oracle_unpack_downlink",
+                     "oracle_pack_uplink", "oracle_unpack_uplink"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -221,3 +224,107 @@ def resample_sparse(draft_logits: np.ndarray, V: int, T: float, seq_off: np.ndar
 
 def record_bytes() -> int:
     return lib().oracle_record_bytes()
+
+
+# ---- wire messages (picospec_wire_oracle.c)
+
+WIRE_FP32, WIRE_FP16, WIRE_BF16 = 0, 1, 2
+WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
+
+
+def wire_quantise(values: np.ndarray, fmt: int):
+    """fp32 -> (bits uint16, value read back float64) in the wire's fp16 or bf16."""
+    v = np.ascontiguousarray(values, np.float32).ravel()
+    bits, back = np.empty(v.size, np.uint16), np.empty(v.size, np.float64)
+    rc = lib().oracle_wire_quantise(_ptr(v), C.c_int32(v.size), C.c_int(fmt), _ptr(bits), _ptr(back))
+    if rc != 0:
+        raise ValueError(f"oracle_wire_quantise rc={rc}")
+    return bits, back
+
+
+def pack_downlink(seq_off: np.ndarray, n_accept: np.ndarray, token: np.ndarray | None,
+                  idx: np.ndarray | None, prob: np.ndarray | None, count: np.ndarray | None,
+                  fmt: int, capacity: int | None = None):
+    """-> (message bytes uint8 [wire_bytes], wire_bytes); the record arrays are [B,k] int32 / float32."""
+    seq_off = np.ascontiguousarray(seq_off, np.int32)
+    B = seq_off.shape[0] - 1
+    n_accept = np.ascontiguousarray(n_accept, np.int32)
+    token = None if token is None else np.ascontiguousarray(token, np.int32)
+    k = 0
+    if idx is not None:
+        idx = np.ascontiguousarray(idx, np.int32)
+        prob = np.ascontiguousarray(prob, np.float32)
+        count = np.ascontiguousarray(count, np.int32)
+        k = idx.shape[1]
+        assert idx.shape == (B, k) and prob.shape == (B, k) and count.shape == (B,)
+    cap = 8 + 8 * B + 8 * B * k + 4 if capacity is None else capacity
+    wire = np.full(max(cap, 1), 0xEE, np.uint8)
+    nbytes = C.c_int64(0)
+    rc = lib().oracle_pack_downlink(C.c_int32(B), _ptr(seq_off), _ptr(n_accept), _ptr(token), _ptr(idx), _ptr(prob),
+                                    _ptr(count), C.c_int32(k), C.c_int(fmt), _ptr(wire), C.c_int64(cap),
+                                    C.byref(nbytes))
+    if rc < 0:
+        raise ValueError(f"oracle_pack_downlink rc={rc}")
+    return (wire[:nbytes.value].copy() if rc == 0 else None), nbytes.value
+
+
+@dataclass
+class Downlink:
+    n_accept: np.ndarray   # int32 [B]
+    token: np.ndarray      # int32 [B]
+    idx: np.ndarray        # int32 [B,k]
+    prob: np.ndarray       # float64 [B,k]
+    count: np.ndarray      # int32 [B]
+    mass: np.ndarray       # float64 [B]
+    status: int
+
+
+def unpack_downlink(wire: np.ndarray, B: int, k: int) -> Downlink:
+    wire = np.ascontiguousarray(wire, np.uint8)
+    out = Downlink(np.full(B, -7, np.int32), np.full(B, -7, np.int32), np.full((B, k), -7, np.int32),
+                   np.full((B, k), -7.0, np.float64), np.full(B, -7, np.int32), np.full(B, -7.0, np.float64), 0)
+    st = C.c_uint32(0)
+    rc = lib().oracle_unpack_downlink(_ptr(wire), C.c_int64(wire.size), C.c_int32(B), C.c_int32(k),
+                                      _ptr(out.n_accept), _ptr(out.token), _ptr(out.idx), _ptr(out.prob),
+                                      _ptr(out.count), _ptr(out.mass), C.byref(st))
+    if rc != 0:
+        raise ValueError(f"oracle_unpack_downlink rc={rc}")
+    out.status = st.value
+    return out
+
+
+def pack_uplink(seq_off: np.ndarray, draft_tok: np.ndarray, q_scalar: np.ndarray, fmt: int,
+                capacity: int | None = None):
+    seq_off = np.ascontiguousarray(seq_off, np.int32)
+    B = seq_off.shape[0] - 1
+    draft_tok = np.ascontiguousarray(draft_tok, np.int32)
+    q_scalar = np.ascontiguousarray(q_scalar, np.float32)
+    N = int(seq_off[-1])
+    cap = 8 + 2 * B + 4 + 8 * N + 4 if capacity is None else capacity
+    wire = np.full(max(cap, 1), 0xEE, np.uint8)
+    nbytes = C.c_int64(0)
+    rc = lib().oracle_pack_uplink(C.c_int32(B), _ptr(seq_off), _ptr(draft_tok), _ptr(q_scalar), C.c_int(fmt),
+                                  _ptr(wire), C.c_int64(cap), C.byref(nbytes))
+    if rc < 0:
+        raise ValueError(f"oracle_pack_uplink rc={rc}")
+    return (wire[:nbytes.value].copy() if rc == 0 else None), nbytes.value
+
+
+@dataclass
+class Uplink:
+    seq_off: np.ndarray    # int32 [B+1]
+    draft_tok: np.ndarray  # int32 [n_max]
+    q_scalar: np.ndarray   # float64 [n_max]
+    status: int
+
+
+def unpack_uplink(wire: np.ndarray, B: int, n_max: int) -> Uplink:
+    wire = np.ascontiguousarray(wire, np.uint8)
+    out = Uplink(np.full(B + 1, -7, np.int32), np.full(n_max, -7, np.int32), np.full(n_max, -7.0, np.float64), 0)
+    st = C.c_uint32(0)
+    rc = lib().oracle_unpack_uplink(_ptr(wire), C.c_int64(wire.size), C.c_int32(B), C.c_int32(n_max),
+                                    _ptr(out.seq_off), _ptr(out.draft_tok), _ptr(out.q_scalar), C.byref(st))
+    if rc != 0:
+        raise ValueError(f"oracle_unpack_uplink rc={rc}")
+    out.status = st.value
+    return out
