@@ -11,6 +11,8 @@
  *   picospec_row_stats / picospec_compress_rejected / picospec_resample_sparse
  *                            the paper's own downlink: Top-K record of the target row at the
  *                            rejected position, local resampling at the edge (Section 3.3, Eq. 4)
+ *   picospec_pack_uplink / picospec_unpack_uplink / picospec_pack_downlink / picospec_unpack_downlink
+ *                            the two messages of a round as contiguous, in-place addressable buffers
  *
  * Conventions shared by all calls
  *   - Every data pointer is a DEVICE pointer (HBM) unless marked "host".  The caller owns all
@@ -190,6 +192,82 @@ int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, in
                              int32_t k, int renorm, const float* uniforms,
                              int32_t* out_tok, float* resid_mass, uint32_t* flags,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- Wire messages of a round (Section 3.3) ----------------------------------------------------
+ * Uplink (edge -> cloud): the drafted tokens and only their own probabilities q_1..q_gamma, 8 bytes
+ * per drafted token with fp32 probabilities (48 bytes at gamma = 6).  Downlink (cloud -> edge): per
+ * sequence the number of accepted tokens and, only if a draft token was rejected, the Top-K record
+ * of Eq. 4 (8 bytes per entry; 80 bytes at K = 10), else the token the cloud decided itself.
+ * The paper names a zero-copy serialisation but prints no byte layout; this is the library's.  Every
+ * block is naturally aligned behind a fixed header, so a receiver addresses the arrays in place.
+ * All fields little-endian; probabilities fp32, or fp16 / bf16 rounded to nearest even:
+ *
+ *   downlink   0  u16 magic 0x5350   2  u8 version (1)   3  u8 prob_format   4  u32 B
+ *              8  B entries of 8 bytes: u16 n_accept, u16 count, i32 token
+ *                 (count entries of this sequence follow below; token = -1 unless count = 0)
+ *              .. int32 ids[total], total = sum of count, sequences in order
+ *              .. prob[total] in prob_format, then zero bytes up to a multiple of 4
+ *   uplink     0  u16 magic 0x5351   2  u8 version (1)   3  u8 prob_format   4  u32 B
+ *              8  u16 gamma[B], zero bytes up to a multiple of 4
+ *              .. int32 tok[N], N = sum of gamma;  q[N] in prob_format, zero bytes up to a multiple of 4
+ *
+ * `wire` is a DEVICE buffer, 4-byte aligned (the caller moves it to and from the NIC or host).
+ * status (device, one uint32) receives a bit set of PICOSPEC_WIRE_*; with BAD_HEADER, BAD_BATCH or
+ * TRUNCATED an unpacking call writes nothing else.
+ */
+enum { PICOSPEC_WIRE_FP32 = 0, PICOSPEC_WIRE_FP16 = 1, PICOSPEC_WIRE_BF16 = 2 };
+enum {
+    PICOSPEC_WIRE_BAD_HEADER = 1u, /* magic, version or prob_format not as expected */
+    PICOSPEC_WIRE_BAD_BATCH = 2u,  /* B in the message differs from the caller's */
+    PICOSPEC_WIRE_CLAMPED = 4u,    /* a record longer than the receiver's k (front kept), or more positions than n_max */
+    PICOSPEC_WIRE_TRUNCATED = 8u   /* the buffer is shorter than the message (unpack) or than the message needs (pack) */
+};
+
+/* host: size of the largest downlink message for B sequences with records of k slots / exact size of
+ * the uplink message for B sequences and n_draft positions; -1 for arguments out of range. */
+int64_t picospec_downlink_bytes_max(int32_t B, int32_t k, int prob_format);
+int64_t picospec_uplink_bytes(int32_t B, int32_t n_draft, int prob_format);
+
+/*
+ * Packs the downlink message of a round.  Sequence b carries its record (idx/prob/count row b, as
+ * picospec_compress_rejected wrote it) iff n_accept[b] < gamma_b; every other sequence carries
+ * token[b] (the bonus token, or a correction the cloud drew itself), -1 if token is NULL.
+ * idx, prob and count may all be NULL: tokens only, 8 bytes per sequence.
+ *   seq_off [B+1], n_accept [B] in; token [B] in, nullable; idx, prob [B,k], count [B] in, nullable together
+ *   wire out, wire_capacity bytes; *wire_bytes (device int64) = size of the message;
+ *   *status = 0, or TRUNCATED when the message exceeds wire_capacity (then only wire_bytes and status are written)
+ * Each workgroup sums the counts in front of its sequence: O(B) per sequence, meant for batch sizes.
+ */
+int picospec_pack_downlink(int32_t B, const int32_t* seq_off, const int32_t* n_accept, const int32_t* token,
+                           const int32_t* idx, const float* prob, const int32_t* count, int32_t k,
+                           int prob_format, void* wire, int64_t wire_capacity,
+                           int64_t* wire_bytes, uint32_t* status, void* stream);
+
+/*
+ * Unpacks a downlink message of wire_bytes bytes (host value: the received length) into the record
+ * layout picospec_resample_sparse takes: idx/prob [B,k] (unused slots -1 / 0, probabilities widened
+ * to fp32 exactly), count, mass = sum of the received probabilities; n_accept and token [B].
+ */
+int picospec_unpack_downlink(const void* wire, int64_t wire_bytes, int32_t B, int32_t k,
+                             int32_t* n_accept, int32_t* token, int32_t* idx, float* prob, int32_t* count,
+                             float* mass, uint32_t* status, void* stream);
+
+/*
+ * Packs the uplink message: gamma_b = seq_off[b+1] - seq_off[b] (<= 65535), the drafted tokens and
+ * their probabilities (q_scalar of picospec_sample_draft).  wire_capacity >= picospec_uplink_bytes().
+ */
+int picospec_pack_uplink(int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                         const float* q_scalar, int prob_format, void* wire, int64_t wire_capacity,
+                         int64_t* wire_bytes, void* stream);
+
+/*
+ * Unpacks an uplink message: seq_off [B+1] (from 0), draft_tok and q_scalar (fp32) for at most n_max
+ * positions.  Sequences are kept whole: the first that does not fit n_max, and all behind it, come
+ * out empty (CLAMPED).  seq_off, draft_tok, q_scalar then feed picospec_verify.
+ */
+int picospec_unpack_uplink(const void* wire, int64_t wire_bytes, int32_t B, int32_t n_max,
+                           int32_t* seq_off, int32_t* draft_tok, float* q_scalar, uint32_t* status, void* stream);
 
 /* host: bytes of device workspace the given call needs for (dtype, rows, V, k); 0 if none. */
 size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k);

@@ -20,9 +20,13 @@ OK, EINVAL, EWORKSPACE, EDTYPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 FLAG_TOKEN_NOT_IN_SUPPORT, FLAG_NONFINITE, FLAG_RESIDUAL_EMPTY, FLAG_BAD_INPUT = 1, 2, 4, 8
 CALL_COMPRESS, CALL_SAMPLE_DRAFT, CALL_VERIFY, CALL_SAMPLE_RESIDUAL = 0, 1, 2, 3
 LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
+WIRE_FP32, WIRE_FP16, WIRE_BF16 = 0, 1, 2
+WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 
 EXPORTS = ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
+           "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
+           "picospec_downlink_bytes_max", "picospec_uplink_bytes",
            "picospec_workspace_bytes", "picospec_limit", "picospec_strerror", "picospec_version")
 
 if not os.path.exists(LIB_PATH):
@@ -43,6 +47,14 @@ lib.picospec_compress_rejected.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i
                                            _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_resample_sparse.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
                                          _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_pack_downlink.argtypes = [_i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int, _p, _i64, _p, _p, _p]
+lib.picospec_unpack_downlink.argtypes = [_p, _i64, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p]
+lib.picospec_pack_uplink.argtypes = [_i32, _i32, _p, _p, _p, C.c_int, _p, _i64, _p, _p]
+lib.picospec_unpack_uplink.argtypes = [_p, _i64, _i32, _i32, _p, _p, _p, _p, _p]
+lib.picospec_downlink_bytes_max.argtypes = [_i32, _i32, C.c_int]
+lib.picospec_downlink_bytes_max.restype = _i64
+lib.picospec_uplink_bytes.argtypes = [_i32, _i32, C.c_int]
+lib.picospec_uplink_bytes.restype = _i64
 lib.picospec_workspace_bytes.argtypes = [C.c_int, C.c_int, _i32, _i32, _i32]
 lib.picospec_workspace_bytes.restype = _sz
 lib.picospec_limit.argtypes = [C.c_int]
@@ -50,7 +62,8 @@ lib.picospec_limit.restype = _i64
 lib.picospec_strerror.argtypes = [C.c_int]
 lib.picospec_strerror.restype = C.c_char_p
 for _n in ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
-           "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse", "picospec_version"):
+           "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse", "picospec_version",
+           "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink"):
     getattr(lib, _n).restype = C.c_int
 
 
@@ -222,6 +235,75 @@ def resample_sparse(draft_logits: torch.Tensor, V: int, temperature: float, seq_
                                         _ptr(uniforms), _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
                                         None, 0, _stream()))
     return out
+
+
+def downlink_bytes_max(B: int, k: int, prob_format: int) -> int:
+    return lib.picospec_downlink_bytes_max(B, k, prob_format)
+
+
+def uplink_bytes(B: int, n_draft: int, prob_format: int) -> int:
+    return lib.picospec_uplink_bytes(B, n_draft, prob_format)
+
+
+def pack_downlink(seq_off: torch.Tensor, n_accept: torch.Tensor, token: torch.Tensor | None,
+                  rec: Compressed | None, prob_format: int, wire: torch.Tensor | None = None):
+    """picospec_pack_downlink -> (wire uint8 [capacity], wire_bytes int64 [1], status int32 [1]), all on device."""
+    B = seq_off.shape[0] - 1
+    k = rec.k if rec is not None else 0
+    dev = seq_off.device
+    if wire is None:
+        wire = torch.empty(downlink_bytes_max(B, k, prob_format), dtype=torch.uint8, device=dev)
+    nbytes = torch.empty(1, dtype=torch.int64, device=dev)
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    _check(lib.picospec_pack_downlink(B, _ptr(seq_off), _ptr(n_accept), _ptr(token),
+                                      _ptr(rec.idx) if rec else None, _ptr(rec.prob) if rec else None,
+                                      _ptr(rec.count) if rec else None, k, prob_format,
+                                      _ptr(wire), wire.numel(), _ptr(nbytes), _ptr(status), _stream()))
+    return wire, nbytes, status
+
+
+@dataclass
+class Downlink:
+    n_accept: torch.Tensor   # int32 [B]
+    token: torch.Tensor      # int32 [B]
+    rec: Compressed          # idx/prob [B,k], count, mass (lse unused)
+    status: torch.Tensor     # int32 [1]
+
+
+def unpack_downlink(wire: torch.Tensor, wire_bytes: int, B: int, k: int) -> Downlink:
+    """picospec_unpack_downlink; `wire_bytes` is the received length (a host value)."""
+    dev = wire.device
+    out = Downlink(torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+                   alloc_compressed(B, k, dev), torch.empty(1, dtype=torch.int32, device=dev))
+    _check(lib.picospec_unpack_downlink(_ptr(wire), wire_bytes, B, k, _ptr(out.n_accept), _ptr(out.token),
+                                        _ptr(out.rec.idx), _ptr(out.rec.prob), _ptr(out.rec.count),
+                                        _ptr(out.rec.mass), _ptr(out.status), _stream()))
+    return out
+
+
+def pack_uplink(seq_off: torch.Tensor, n_draft: int, draft_tok: torch.Tensor, q_scalar: torch.Tensor,
+                prob_format: int, wire: torch.Tensor | None = None):
+    """picospec_pack_uplink -> (wire uint8, wire_bytes int64 [1]) on device."""
+    B = seq_off.shape[0] - 1
+    dev = seq_off.device
+    if wire is None:
+        wire = torch.empty(uplink_bytes(B, n_draft, prob_format), dtype=torch.uint8, device=dev)
+    nbytes = torch.empty(1, dtype=torch.int64, device=dev)
+    _check(lib.picospec_pack_uplink(B, n_draft, _ptr(seq_off), _ptr(draft_tok), _ptr(q_scalar), prob_format,
+                                    _ptr(wire), wire.numel(), _ptr(nbytes), _stream()))
+    return wire, nbytes
+
+
+def unpack_uplink(wire: torch.Tensor, wire_bytes: int, B: int, n_max: int):
+    """picospec_unpack_uplink -> (seq_off int32 [B+1], draft_tok int32 [n_max], q_scalar float32 [n_max], status)."""
+    dev = wire.device
+    seq_off = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    tok = torch.empty(n_max, dtype=torch.int32, device=dev)
+    q = torch.empty(n_max, dtype=torch.float32, device=dev)
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    _check(lib.picospec_unpack_uplink(_ptr(wire), wire_bytes, B, n_max, _ptr(seq_off), _ptr(tok), _ptr(q),
+                                      _ptr(status), _stream()))
+    return seq_off, tok, q, status
 
 
 def workspace_bytes(which: int, dtype: int, rows: int, V: int, k: int) -> int:

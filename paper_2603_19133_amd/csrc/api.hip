@@ -99,6 +99,75 @@ int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, in
                                              uniforms, out_tok, resid_mass, flags, (hipStream_t)stream));
 }
 
+// ---- wire messages
+
+namespace {
+bool wire_format_ok(int f) { return f == PICOSPEC_WIRE_FP32 || f == PICOSPEC_WIRE_FP16 || f == PICOSPEC_WIRE_BF16; }
+bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
+}  // namespace
+
+int64_t picospec_downlink_bytes_max(int32_t B, int32_t k, int prob_format)
+{
+    if (B < 0 || k < 0 || k > kMaxK || !wire_format_ok(prob_format)) return -1;
+    return downlink_bytes_max(B, k, prob_format);
+}
+
+int64_t picospec_uplink_bytes(int32_t B, int32_t n_draft, int prob_format)
+{
+    if (B < 0 || n_draft < 0 || !wire_format_ok(prob_format)) return -1;
+    return uplink_bytes(B, n_draft, prob_format);
+}
+
+int picospec_pack_downlink(int32_t B, const int32_t* seq_off, const int32_t* n_accept, const int32_t* token,
+                           const int32_t* idx, const float* prob, const int32_t* count, int32_t k,
+                           int prob_format, void* wire, int64_t wire_capacity,
+                           int64_t* wire_bytes, uint32_t* status, void* stream)
+{
+    if (B < 0 || !wire_format_ok(prob_format)) return PICOSPEC_EINVAL;
+    const bool records = idx || prob || count;
+    if (records && (!idx || !prob || !count || k < 1)) return PICOSPEC_EINVAL;
+    if (records && k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (!wire || !aligned4(wire) || wire_capacity < 8 || !wire_bytes || !status) return PICOSPEC_EINVAL;
+    if (B > 0 && (!seq_off || !n_accept)) return PICOSPEC_EINVAL;
+    return hip_status(launch_pack_downlink(B, seq_off, n_accept, token, idx, prob, count, records ? k : 0, prob_format,
+                                           wire, wire_capacity, wire_bytes, status, (hipStream_t)stream));
+}
+
+int picospec_unpack_downlink(const void* wire, int64_t wire_bytes, int32_t B, int32_t k,
+                             int32_t* n_accept, int32_t* token, int32_t* idx, float* prob, int32_t* count,
+                             float* mass, uint32_t* status, void* stream)
+{
+    if (B < 0 || k < 1 || wire_bytes < 0) return PICOSPEC_EINVAL;
+    if (k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (!status || (wire_bytes > 0 && (!wire || !aligned4(wire)))) return PICOSPEC_EINVAL;
+    if (B > 0 && (!n_accept || !token || !idx || !prob || !count || !mass)) return PICOSPEC_EINVAL;
+    return hip_status(launch_unpack_downlink(wire, wire_bytes, B, k, n_accept, token, idx, prob, count, mass, status,
+                                             (hipStream_t)stream));
+}
+
+int picospec_pack_uplink(int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                         const float* q_scalar, int prob_format, void* wire, int64_t wire_capacity,
+                         int64_t* wire_bytes, void* stream)
+{
+    if (B < 0 || n_draft < 0 || !wire_format_ok(prob_format)) return PICOSPEC_EINVAL;
+    if (!wire || !aligned4(wire) || !wire_bytes) return PICOSPEC_EINVAL;
+    if (wire_capacity < uplink_bytes(B, n_draft, prob_format)) return PICOSPEC_EINVAL;
+    if (B > 0 && !seq_off) return PICOSPEC_EINVAL;
+    if (n_draft > 0 && (!draft_tok || !q_scalar)) return PICOSPEC_EINVAL;
+    return hip_status(launch_pack_uplink(B, n_draft, seq_off, draft_tok, q_scalar, prob_format, wire, wire_bytes,
+                                         (hipStream_t)stream));
+}
+
+int picospec_unpack_uplink(const void* wire, int64_t wire_bytes, int32_t B, int32_t n_max,
+                           int32_t* seq_off, int32_t* draft_tok, float* q_scalar, uint32_t* status, void* stream)
+{
+    if (B < 0 || n_max < 0 || wire_bytes < 0) return PICOSPEC_EINVAL;
+    if (!status || !seq_off || (wire_bytes > 0 && (!wire || !aligned4(wire)))) return PICOSPEC_EINVAL;
+    if (n_max > 0 && (!draft_tok || !q_scalar)) return PICOSPEC_EINVAL;
+    return hip_status(launch_unpack_uplink(wire, wire_bytes, B, n_max, seq_off, draft_tok, q_scalar, status,
+                                           (hipStream_t)stream));
+}
+
 int picospec_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
                           int32_t k, int32_t n_rows, const float* uniforms,
                           int32_t* tok, float* q_scalar, void* stream)

@@ -59,4 +59,22 @@ hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t l
                                   int k, int renorm, const float* uniforms,
                                   int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
 
+// ---- wire messages (csrc/wire.hip); fmt: 0 fp32, 1 fp16, 2 bf16 probabilities
+int64_t downlink_bytes_max(int B, int k, int fmt);
+int64_t uplink_bytes(int B, int n_draft, int fmt);
+
+hipError_t launch_pack_downlink(int B, const int32_t* seq_off, const int32_t* n_accept, const int32_t* token,
+                                const int32_t* idx, const float* prob, const int32_t* count, int k, int fmt,
+                                void* wire, int64_t capacity, int64_t* wire_bytes, uint32_t* status, hipStream_t stream);
+
+hipError_t launch_unpack_downlink(const void* wire, int64_t wire_bytes, int B, int k, int32_t* n_accept,
+                                  int32_t* token, int32_t* idx, float* prob, int32_t* count, float* mass,
+                                  uint32_t* status, hipStream_t stream);
+
+hipError_t launch_pack_uplink(int B, int n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                              const float* q_scalar, int fmt, void* wire, int64_t* wire_bytes, hipStream_t stream);
+
+hipError_t launch_unpack_uplink(const void* wire, int64_t wire_bytes, int B, int n_max, int32_t* seq_off,
+                                int32_t* draft_tok, float* q_scalar, uint32_t* status, hipStream_t stream);
+
 }  // namespace picospec

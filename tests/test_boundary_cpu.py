@@ -163,6 +163,46 @@ def test_downlink_calls_reject_misuse(B):
     assert res(outs=(None, FAKE, FAKE)) == B.EINVAL and res(T=float("nan")) == B.EINVAL
 
 
+def test_wire_calls_reject_misuse_and_report_sizes(B):
+    """Host-visible misuse of the wire calls returns an error code before any launch; the size helpers give
+    the paper's payload arithmetic (Section 3.3: 8 bytes per entry / per drafted token) plus the headers."""
+    lib = B.lib
+    assert B.downlink_bytes_max(1, 10, B.WIRE_FP32) == 8 + 8 + 80 and B.downlink_bytes_max(1, 10, B.WIRE_FP16) == 8 + 8 + 60
+    assert B.downlink_bytes_max(3, 5, B.WIRE_BF16) == 8 + 24 + 92 and B.downlink_bytes_max(0, 7, 0) == 8
+    assert B.downlink_bytes_max(1, 10, 3) == -1 and B.downlink_bytes_max(-1, 10, 0) == -1 and B.downlink_bytes_max(1, 5000, 0) == -1
+    assert B.uplink_bytes(1, 6, B.WIRE_FP32) == 8 + 4 + 48 and B.uplink_bytes(1, 6, B.WIRE_FP16) == 48
+    assert B.uplink_bytes(3, 7, B.WIRE_BF16) == 8 + 8 + 28 + 16 and B.uplink_bytes(2, 3, 9) == -1
+    odd = C.c_void_p(0x1002)
+
+    def pd(Bn=2, seq=FAKE, na=FAKE, tok=FAKE, rec=(FAKE, FAKE, FAKE), k=8, fmt=0, wire=FAKE, cap=4096, nb=FAKE, st=FAKE):
+        return lib.picospec_pack_downlink(Bn, seq, na, tok, *rec, k, fmt, wire, cap, nb, st, None)
+
+    assert pd(Bn=-1) == B.EINVAL and pd(fmt=3) == B.EINVAL and pd(seq=None) == B.EINVAL and pd(na=None) == B.EINVAL
+    assert pd(rec=(FAKE, None, FAKE)) == B.EINVAL and pd(k=0) == B.EINVAL and pd(k=5000) == B.EUNSUPPORTED
+    assert pd(wire=None) == B.EINVAL and pd(wire=odd) == B.EINVAL and pd(cap=4) == B.EINVAL
+    assert pd(nb=None) == B.EINVAL and pd(st=None) == B.EINVAL
+
+    def ud(wire=FAKE, n=64, Bn=2, k=8, outs=(FAKE,) * 6, st=FAKE):
+        return lib.picospec_unpack_downlink(wire, n, Bn, k, *outs, st, None)
+
+    assert ud(wire=None) == B.EINVAL and ud(wire=odd) == B.EINVAL and ud(n=-1) == B.EINVAL and ud(Bn=-1) == B.EINVAL
+    assert ud(k=0) == B.EINVAL and ud(k=5000) == B.EUNSUPPORTED and ud(st=None) == B.EINVAL
+    assert ud(outs=(FAKE, FAKE, None, FAKE, FAKE, FAKE)) == B.EINVAL
+
+    def pu(Bn=2, N=6, seq=FAKE, tok=FAKE, q=FAKE, fmt=0, wire=FAKE, cap=4096, nb=FAKE):
+        return lib.picospec_pack_uplink(Bn, N, seq, tok, q, fmt, wire, cap, nb, None)
+
+    assert pu(Bn=-1) == B.EINVAL and pu(N=-1) == B.EINVAL and pu(fmt=-1) == B.EINVAL and pu(seq=None) == B.EINVAL
+    assert pu(tok=None) == B.EINVAL and pu(q=None) == B.EINVAL and pu(wire=None) == B.EINVAL and pu(wire=odd) == B.EINVAL
+    assert pu(cap=B.uplink_bytes(2, 6, 0) - 1) == B.EINVAL and pu(nb=None) == B.EINVAL
+
+    def uu(wire=FAKE, n=64, Bn=2, nmax=6, seq=FAKE, tok=FAKE, q=FAKE, st=FAKE):
+        return lib.picospec_unpack_uplink(wire, n, Bn, nmax, seq, tok, q, st, None)
+
+    assert uu(wire=None) == B.EINVAL and uu(wire=odd) == B.EINVAL and uu(n=-1) == B.EINVAL and uu(Bn=-1) == B.EINVAL
+    assert uu(nmax=-1) == B.EINVAL and uu(seq=None) == B.EINVAL and uu(tok=None) == B.EINVAL and uu(st=None) == B.EINVAL
+
+
 def test_compress_kernels_keep_everything_in_registers():
     """The compress kernel issues LDS atomics and loads by hand and reads their results later; a register
     spilled in between would carry a stale value.  The build must therefore report no vector-register
