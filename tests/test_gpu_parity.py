@@ -237,6 +237,43 @@ def test_ragged_small_rounds(gpu, pu, renorm, dtype):
         assert 0 < o.ver.n_accept.sum() < N
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_round_at_the_largest_vocabulary_and_record(gpu, pu, ps, dtype):
+    """The limits the library reports (V = 2^20, k = 4096): one small ragged round, compress, verify and the
+    residual draw, and the downlink's record of the rejected rows at the same size."""
+    V, k = ps.limit(ps.LIMIT_MAX_V), ps.limit(ps.LIMIT_MAX_K)
+    _announce("largest sizes", V, k, dtype)
+    assert (V, k) == (1 << 20, 4096)
+    rng = np.random.default_rng(77)
+    g = np.array([2, 0, 1], np.int32)
+    off = W.seq_offsets(g)
+    N, B = int(off[-1]), len(g)
+    tgt = (rng.standard_normal((N + B, V)) * 4).astype(np.float32)
+    draft = np.empty((N, V), np.float32)
+    for b in range(B):
+        for i in range(g[b]):
+            draft[off[b] + i] = tgt[off[b] + b + i] + rng.standard_normal(V).astype(np.float32)
+    if dtype == "bf16":
+        tgt, draft = W.to_bf16_bits(tgt), W.to_bf16_bits(draft)
+    w = W.Workload("largest", 92, B, 0, 2, V, dtype, 1.1, k, 0.0, 1, "custom")
+    r = _custom_round(w, draft, tgt, off, rng.random(N + B, dtype=np.float32), rng.random(N, dtype=np.float32))
+    o = pu.oracle_round(r)
+    gq = pu.gpu_round(r, o.tok, gpu)
+    pu.compare_round(gq, o, r, max_excluded_frac=0.34)
+    orec = oracle.compress_rejected(r.tgt_logits, V, w.T, r.seq_off, o.ver.n_accept, k)
+    grec = ps.compress_rejected(pu.to_device(r.tgt_logits, gpu), V, w.T, torch.from_numpy(r.seq_off).to(gpu), N,
+                                torch.from_numpy(o.ver.n_accept).to(gpu), k)
+    torch.cuda.synchronize()
+    pu.compare_compress(grec, orec)
+    # one past the limits is refused, not attempted
+    with pytest.raises(ps.PicoSpecError) as e:
+        ps.compress(torch.zeros((1, V + 1), device=gpu), V + 1, 1.0, 8)
+    assert e.value.code == ps.EUNSUPPORTED
+    with pytest.raises(ps.PicoSpecError) as e:
+        ps.compress(torch.zeros((1, 8192), device=gpu), 8192, 1.0, k + 1)
+    assert e.value.code == ps.EUNSUPPORTED
+
+
 def test_scalar_q_uplink_and_foreign_tokens(gpu, pu, ps):
     """The edge's scalar q_i replaces the sparse lookup; tokens outside the record are accepted and flagged."""
     _announce("scalar q / foreign tokens")
