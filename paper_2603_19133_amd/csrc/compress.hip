@@ -557,7 +557,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     // few lanes per instruction) and later writes (value, id) there.  Both steps are hand-issued so
     // that they stay straight-line code (predication by EXEC, no branches for the compiler to lay
     // out): claim_asm forms the lane mask, claims under it and hands the mask on; put_asm waits for
-    // the claimed slots and writes under the same masks, skipping columns nobody passed.  The counter
+    // the claimed slots and writes under the same masks.  The counter
     // counts bytes of cand_val (4 per candidate) so that a masked slot is the LDS address; slots wrap
     // around the buffer: once the count has passed its end the pass is lost anyway.
     typedef __attribute__((address_space(3))) unsigned lds_u32;
@@ -594,26 +594,26 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             asm volatile("" : "+v"(slot[8]), "+v"(slot[9]), "+v"(slot[10]), "+v"(slot[11]),
                          "+v"(slot[12]), "+v"(slot[13]), "+v"(slot[14]), "+v"(slot[15]));
         }
+        // addresses and ids of all columns first (every lane, back to back), then only the write under each mask
         const unsigned va = val_addr;
+        unsigned at[NVV * N], id[NVV * N];
 #pragma unroll
         for (int j = 0; j < NVV; ++j)
 #pragma unroll
             for (int e = 0; e < N; ++e) {
-                unsigned long long saved;
-                unsigned at, id;
-                asm volatile("s_and_saveexec_b64 %[sv], %[m]\n\t"
-                             "s_cbranch_execz .Lskip%=\n\t"
-                             "v_and_b32 %[at], %[slot], %[wrap]\n\t"
-                             "v_add_u32 %[at], %[va], %[at]\n\t"
-                             "v_add_u32 %[id], %[c], %[x0]\n\t"
-                             "ds_write2st64_b32 %[at], %[x], %[id] offset1:128\n"
-                             ".Lskip%=:\n\t"
-                             "s_mov_b64 exec, %[sv]"
-                             : [sv] "=&s"(saved), [at] "=&v"(at), [id] "=&v"(id)
-                             : [m] "s"(passed[j * N + e]), [slot] "v"(slot[j * N + e]), [wrap] "v"(wrap), [va] "s"(va),
-                               [c] "s"(j * kT * N + e), [x0] "v"(x0), [x] "v"(v[j * N + e])
-                             : "memory", "scc");
+                at[j * N + e] = ((unsigned)slot[j * N + e] & wrap) + va;
+                id[j * N + e] = (unsigned)(x0 + j * kT * N + e);
             }
+#pragma unroll
+        for (int i = 0; i < NVV * N; ++i) {
+            unsigned long long saved;
+            asm volatile("s_and_saveexec_b64 %[sv], %[m]\n\t"
+                         "ds_write2st64_b32 %[at], %[x], %[id] offset1:128\n\t"
+                         "s_mov_b64 exec, %[sv]"
+                         : [sv] "=&s"(saved)
+                         : [m] "s"(passed[i]), [at] "v"(at[i]), [id] "v"(id[i]), [x] "v"(v[i])
+                         : "memory", "scc");
+        }
     };
     static_assert(offsetof(CompressShared, cand_id) - offsetof(CompressShared, cand_val) == 128 * 64 * 4,
                   "ds_write2st64 offset1:128 reaches cand_id from cand_val");
