@@ -18,8 +18,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wal
          "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
-def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    cmd = [HIPCC, *FLAGS, *(extra or []), "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+def build(verbose: bool = False, extra: list[str] | None = None, out: str | None = None) -> str:
+    """Compiles the library (to `out` instead of the in-tree libpicospec.so, if given)."""
+    out = out or LIB
+    cmd = [HIPCC, *FLAGS, *(extra or []), "-o", out, *[os.path.join(CSRC, s) for s in SOURCES]]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -29,7 +31,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -269,7 +269,13 @@ __device__ __forceinline__ void order_prepare(CompressShared& sh, int n) {
 //     its bin is the number of larger bin-mates, and the positions below k are kept.
 // A bin too crowded for that sends the row through the radix select and a sorting network.
 template <bool BF16>
-__device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi) {
+__device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi,
+                                                       unsigned long long* stamp_out) {
+#ifdef PICOSPEC_PHASE_CLOCKS
+#define OSTAMP(i) do { if (threadIdx.x == 0) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); stamp_out[i] = wall_clock64(); } } while (0)
+#else
+#define OSTAMP(i) do { (void)stamp_out; } while (0)
+#endif
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     uint64_t* buf = reinterpret_cast<uint64_t*>(sh.cand_val);   // cand_val and cand_id, back to back
     const uint32_t kr = key_hi - key_lo;
@@ -294,6 +300,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();
+    OSTAMP(7);
     // fine bins per coarse range, in proportion to its count (at least one where there is a candidate); one
     // wave builds the table, kCoarse / 64 consecutive ranges per lane
     if (wave == 0) {
@@ -312,6 +319,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         for (int u = 0; u < kPerLane; ++u) { sh.coarse[lane * kPerLane + u] = (nf[u] << 16) | first; first += nf[u]; }
     }
     __syncthreads();
+    OSTAMP(8);
     int meta[kCandPer];                      // (fine bin << 16) | arrival order within the bin; -1: no candidate
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) {
@@ -325,6 +333,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();
+    OSTAMP(9);
     // exclusive prefix over the bins, in place; the bin that holds the k-th largest; the most crowded bin in front of it
     int h[kBinsPer], loc = 0;
 #pragma unroll
@@ -364,12 +373,14 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         bitonic_sort_desc(buf, P);
         return buf;
     }
+    OSTAMP(10);
     const int piv = sh.piv_bin, n_keep = sh.piv_before;
     // gather bin by bin (every candidate is in registers: the buffer may be overwritten)
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j)
         if (meta[j] >= 0 && (meta[j] >> 16) <= piv) buf[(int)sh.hist[meta[j] >> 16] + (meta[j] & 0xFFFF)] = c[j];
     __syncthreads();
+    OSTAMP(11);
     int pos[kCandPer];
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) {
@@ -390,6 +401,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();                         // all positions are known before the ordered list overwrites the bins
+    OSTAMP(12);
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) if (pos[j] < k) buf[pos[j]] = c[j];
     __syncthreads();
@@ -435,6 +447,17 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         const int d0 = seq_off[row], g = max(seq_off[row + 1] - d0, 0);
         in_row = (int64_t)d0 + row + min(max(n_accept[row], 0), g);
     }
+    // Optional timeline (-DPICOSPEC_PHASE_CLOCKS, off in the library): thread 0 of every workgroup stores the
+    // 100 MHz wall clock at the phase boundaries, 16 words per row behind the prob array, which the caller
+    // of such a build must have allocated (python -m paper_2603_19133_amd.phase_clocks does).
+#ifdef PICOSPEC_PHASE_CLOCKS
+    unsigned long long* stamp_out = reinterpret_cast<unsigned long long*>(prob + (int64_t)gridDim.x * k) + (int64_t)blockIdx.x * 16;
+#define STAMP(i) do { if (threadIdx.x == 0) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); stamp_out[i] = wall_clock64(); } } while (0)
+#else
+    unsigned long long* stamp_out = nullptr;
+#define STAMP(i) do {} while (0)
+#endif
+    STAMP(0);
     const RowView rv = row_view<BF16>(logits, ld, in_row, V);
     const int n_sub = (rv.L + SUB - 1) / SUB;
     const int nq = (rv.L + N - 1) / N;           // 16-byte vectors that overlap the row
@@ -644,6 +667,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         {
             float v[E0];
             unpack_vecs(nv0_t{}, tid, &rb[0][0], v, true);
+            STAMP(1);
             const float bm = add_stats(e0_t{}, v, true);
             float bn = __builtin_huge_valf();
 #pragma unroll
@@ -655,6 +679,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             key_hi = 0; key_lo = 0xFFFFFFFFu;
 #pragma unroll
             for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); }
+            STAMP(2);
             const int target = optimistic ? r_opt : k;
             bool have_tau = false;
             if (optimistic && more && n0 > target) {
@@ -684,6 +709,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                         }
                     }
                     __syncthreads();             // (the histogram and the pivot words are reused below)
+                    STAMP(3);
                 }
             }
             if (!have_tau && more && n0 > target && key_hi > key_lo) {
@@ -726,6 +752,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             }
         }
 
+        STAMP(4);
         bool enough = true;
         if (optimistic) {
             // ---- behind the sample, optimistic: waves run free; a reservation that does not fit gives the
@@ -816,6 +843,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         if (!enough) continue;                   // optimistic threshold too high, or buffer full: stream again, safely
 
         // ---- end of row
+        STAMP(5);
         if (n_held < 0) n_held = sh.cnt;
         order_prepare(sh, n_held);               // (the barriers of the combine below stand behind it)
         {   // M = max over the threads; S = sum s * 2^(r - M*c), combined in fp64
@@ -835,6 +863,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             if (tid == kT - 1) lse[row] = (float)((double)M * (double)inv_T + log(S));   // (off the last wave's critical path later on)
         }
         key_hi = short_key<BF16>(__float_as_uint(M));
+        STAMP(6);
         break;
     }
 
@@ -855,7 +884,8 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
 
     // ---- exact cut to k, ordering and emission
     const int n = min(n_held, k);
-    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi);
+    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi, stamp_out);
+    STAMP(13);
 
     // the dropped loads have landed (they were issued a whole ordering ago); waiting here, in front of the
     // record's stores, keeps the wave from waiting for those at its end
@@ -934,6 +964,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             if (keep) { my_mass += (double)pr; ++my_count; }
         }
     }
+    STAMP(14);
     const double wm = wave_sum(my_mass);
     const int wc = wave_sum(my_count);
     if (lane == 0) { sh.red[wave] = wm; sh.red[kW + wave] = (double)wc; }
@@ -944,6 +975,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         mass[row] = (float)tm;
         count[row] = (int)tc;
     }
+    STAMP(15);
 }
 
 // The drafter's draw: inverse CDF over the used slots, one wave per row.
