@@ -121,7 +121,10 @@ class Verified:
 
 def verify(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray, draft_tok: np.ndarray,
            q: Compressed | None, uniforms: np.ndarray, renorm: int = 1,
-           q_scalar: np.ndarray | None = None) -> Verified:
+           q_scalar: np.ndarray | None = None, pos_begin: np.ndarray | None = None,
+           pos_end: np.ndarray | None = None, out: Verified | None = None) -> Verified:
+    """pos_begin / pos_end restrict every sequence to a range of its draft positions; `out` (the result of an
+    earlier call) is then updated in place, entries outside the range keep their values."""
     dt = _logits(tgt_logits)
     rows, ld = tgt_logits.shape
     seq_off = np.ascontiguousarray(seq_off, np.int32)
@@ -132,8 +135,11 @@ def verify(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray, draft_
     u = np.ascontiguousarray(uniforms, np.float32)
     assert draft_tok.shape == (N,) and u.shape[0] >= N + B
     qs = None if q_scalar is None else np.ascontiguousarray(q_scalar, np.float64)
-    out = Verified(np.empty(B, np.int32), np.empty(N, np.float64), np.empty(N, np.float64),
-                   np.empty(N + B, np.float64), np.zeros(B, np.uint32), np.empty(N, np.float64))
+    if out is None:
+        out = Verified(np.full(B, -7, np.int32), np.full(N, np.nan), np.full(N, np.nan),
+                       np.full(N + B, np.nan), np.zeros(B, np.uint32), np.full(N, np.nan))
+    pb = None if pos_begin is None else np.ascontiguousarray(pos_begin, np.int32)
+    pe = None if pos_end is None else np.ascontiguousarray(pos_end, np.int32)
     k = q.k if q is not None else 1
     rc = lib().oracle_verify(_ptr(tgt_logits), C.c_int(dt), C.c_int64(ld), C.c_int32(V), C.c_double(T),
                              C.c_int32(B), _ptr(seq_off), _ptr(draft_tok),
@@ -141,7 +147,7 @@ def verify(tgt_logits: np.ndarray, V: int, T: float, seq_off: np.ndarray, draft_
                              _ptr(q.count) if q else None, _ptr(q.mass) if q else None,
                              C.c_int32(k), C.c_int(renorm), _ptr(qs), _ptr(u),
                              _ptr(out.n_accept), _ptr(out.p_tok), _ptr(out.q_tok), _ptr(out.tgt_lse),
-                             _ptr(out.flags), _ptr(out.margin))
+                             _ptr(out.flags), _ptr(out.margin), _ptr(pb), _ptr(pe))
     if rc != 0:
         raise ValueError(f"oracle_verify rc={rc}")
     return out

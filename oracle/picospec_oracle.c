@@ -202,6 +202,12 @@ int oracle_sample_draft(const int32_t *idx, const double *prob, const int32_t *c
  *   accept_i  <=>  u_i < min(1, p_i / qhat_i);   n_accept[b] = first i not accepted, else gamma_b
  *   q_scalar  nullable [N]: the edge's recorded scalar q_i; overrides the sparse lookup
  *   p_tok, q_tok [N]; tgt_lse [N+B]; flags [B]; margin [N] = |u - p/q| / (p/q)
+ * Verification of a part of the draft (Section 3.2, Fast Verification: the cloud starts on the
+ * positions that are known and goes on when the rest arrives): pos_begin / pos_end, nullable [B],
+ * restrict sequence b to its positions begin_b <= t < end_b (defaults 0 and gamma_b; clamped to
+ * that range).  Target rows begin_b..end_b are read (row end_b is the one behind the last known
+ * position); entries of the outputs for other rows and positions are left as they are;
+ * n_accept[b] = first rejected position in the range, else end_b.
  */
 int oracle_verify(const void *tgt_logits, int dtype, int64_t ld, int32_t V, double T,
                   int32_t B, const int32_t *seq_off, const int32_t *draft_tok,
@@ -209,7 +215,8 @@ int oracle_verify(const void *tgt_logits, int dtype, int64_t ld, int32_t V, doub
                   const double *q_mass, int32_t k, int renorm,
                   const double *q_scalar, const float *uniforms,
                   int32_t *n_accept, double *p_tok, double *q_tok, double *tgt_lse,
-                  uint32_t *flags, double *margin)
+                  uint32_t *flags, double *margin,
+                  const int32_t *pos_begin, const int32_t *pos_end)
 {
     if (!tgt_logits || V < 1 || !(T > 0.0) || ld < V || B < 0) return -1;
     const size_t esz = dtype == ORACLE_F32 ? 4 : 2;
@@ -218,13 +225,18 @@ int oracle_verify(const void *tgt_logits, int dtype, int64_t ld, int32_t V, doub
         int32_t d0 = seq_off[b], gamma = seq_off[b + 1] - seq_off[b];
         int64_t t0 = (int64_t)d0 + b;
         uint32_t fl = 0;
-        int32_t first_reject = gamma;
-        for (int32_t t = 0; t <= gamma; ++t) {
+        int32_t begin = pos_begin ? pos_begin[b] : 0, end = pos_end ? pos_end[b] : gamma;
+        if (end < 0) end = 0;
+        if (end > gamma) end = gamma;
+        if (begin < 0) begin = 0;
+        if (begin > end) begin = end;
+        int32_t first_reject = end;
+        for (int32_t t = begin; t <= end; ++t) {
             const void *row = (const char *)tgt_logits + (size_t)(t0 + t) * (size_t)ld * esz;
             double l = row_lse(row, dtype, V, T);
             tgt_lse[t0 + t] = l;
             if (!isfinite(l)) fl |= ORACLE_FLAG_NONFINITE;
-            if (t == gamma) break; /* bonus row: statistics only */
+            if (t == end) break; /* the row behind the last position (the bonus row when end = gamma): statistics only */
             int32_t i = d0 + t, x = draft_tok[i];
             double p = exp(logit_at(row, dtype, x) / T - l);
             double q;
