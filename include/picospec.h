@@ -7,6 +7,7 @@
  *   picospec_compress        sparse Top-K record of every draft distribution        (Eq. 4)
  *   picospec_sample_draft    the drafter's token draw from that record (edge side, Section 3.3)
  *   picospec_verify          parallel verification: acceptance test, first rejection (Section 3.3)
+ *   picospec_verify_range    the same for a range of each draft's positions (Section 3.2, Fast Verification)
  *   picospec_sample_residual correction token ~ norm(max(0, P_j - Q_j)), or the bonus token
  *   picospec_row_stats / picospec_compress_rejected / picospec_resample_sparse
  *                            the paper's own downlink: Top-K record of the target row at the
@@ -124,6 +125,31 @@ int picospec_verify(const void* tgt_logits, int dtype, int64_t ld, int32_t V, fl
                     int32_t* n_accept, float* p_tok, float* q_tok,
                     float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Verification of a part of the draft (Section 3.2, Fast Verification: the cloud starts on the
+ * positions of a draft that are known and goes on when the rest arrives; Section 3.3 for the test).
+ * picospec_verify restricted, per sequence, to the draft positions begin_b <= t < end_b with
+ * begin_b = pos_begin[b] and end_b = pos_end[b] (either may be NULL: 0 and gamma_b), in the same row
+ * layout: target rows begin_b..end_b are read (row end_b is the one behind the last known position)
+ * and their entries of tgt_max, tgt_sum, tgt_lse written; p_tok, q_tok are written for the
+ * positions of the range; everything else in those arrays keeps what an earlier call left there.
+ *   n_accept[b] = first rejected position of the range, else end_b
+ *   flags[b]    = the conditions met in this range (BAD_INPUT also for a range outside
+ *                 0 <= begin_b <= end_b <= gamma_b, which is clamped)
+ * Consecutive ranges compose: with n' from an earlier call over [begin', end') and n from this one
+ * over [end', end), the sequence's first rejection is n' if n' < end', else n.
+ *   gamma_max  host value >= every gamma_b (<= n_draft): the launch is (gamma_max + 1) x B workgroups,
+ *              B <= 65535
+ */
+int picospec_verify_range(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                          int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                          int32_t k, int renorm, const float* q_scalar, const float* uniforms,
+                          const int32_t* pos_begin, const int32_t* pos_end, int32_t gamma_max,
+                          int32_t* n_accept, float* p_tok, float* q_tok,
+                          float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Correction / bonus token (Section 3.3: norm(max(0, P_j(x) - Q_j(x)))): for sequence b with

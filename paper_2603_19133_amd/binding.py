@@ -23,7 +23,7 @@ LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
 WIRE_FP32, WIRE_FP16, WIRE_BF16 = 0, 1, 2
 WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 
-EXPORTS = ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
+EXPORTS = ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
            "picospec_downlink_bytes_max", "picospec_uplink_bytes",
@@ -40,6 +40,8 @@ lib.picospec_compress.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _i32, _f, _
 lib.picospec_sample_draft.argtypes = [_p, _p, _p, _p, _i32, _i32, _p, _p, _p, _p]
 lib.picospec_verify.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int,
                                 _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_verify_range.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int,
+                                      _p, _p, _p, _p, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_sample_residual.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
                                          _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_row_stats.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _p, _p, _p, _p]
@@ -63,7 +65,8 @@ lib.picospec_strerror.argtypes = [C.c_int]
 lib.picospec_strerror.restype = C.c_char_p
 for _n in ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse", "picospec_version",
-           "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink"):
+           "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
+           "picospec_verify_range"):
     getattr(lib, _n).restype = C.c_int
 
 
@@ -168,6 +171,26 @@ def verify(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.
                                _ptr(out.n_accept), _ptr(out.p_tok), _ptr(out.q_tok),
                                _ptr(out.tgt_max), _ptr(out.tgt_sum), _ptr(out.tgt_lse), _ptr(out.flags),
                                None, 0, _stream()))
+    return out
+
+
+def verify_range(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+                 draft_tok: torch.Tensor, q: Compressed | None, uniforms: torch.Tensor,
+                 pos_begin: torch.Tensor | None, pos_end: torch.Tensor | None, gamma_max: int, renorm: int = 1,
+                 q_scalar: torch.Tensor | None = None, out: Verified | None = None) -> Verified:
+    """picospec_verify_range: the draft positions pos_begin[b] <= t < pos_end[b] only; `out` from an earlier
+    call keeps its entries outside the range."""
+    dt, ld = _logits_2d(tgt_logits)
+    B = seq_off.shape[0] - 1
+    out = out or alloc_verified(B, n_draft, tgt_logits.device)
+    _check(lib.picospec_verify_range(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off), _ptr(draft_tok),
+                                     _ptr(q.idx) if q else None, _ptr(q.prob) if q else None,
+                                     _ptr(q.count) if q else None, _ptr(q.mass) if q else None,
+                                     q.k if q else 0, renorm, _ptr(q_scalar), _ptr(uniforms),
+                                     _ptr(pos_begin), _ptr(pos_end), gamma_max,
+                                     _ptr(out.n_accept), _ptr(out.p_tok), _ptr(out.q_tok),
+                                     _ptr(out.tgt_max), _ptr(out.tgt_sum), _ptr(out.tgt_lse), _ptr(out.flags),
+                                     None, 0, _stream()))
     return out
 
 

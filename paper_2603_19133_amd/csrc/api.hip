@@ -178,13 +178,17 @@ int picospec_sample_draft(const int32_t* idx, const float* prob, const int32_t* 
                                           (hipStream_t)stream));
 }
 
-int picospec_verify(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
-                    int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
-                    const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
-                    int32_t k, int renorm, const float* q_scalar, const float* uniforms,
-                    int32_t* n_accept, float* p_tok, float* q_tok,
-                    float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
-                    void* workspace, size_t workspace_bytes, void* stream)
+namespace {
+
+// picospec_verify and picospec_verify_range share everything but the rows the statistics pass visits.
+int verify_impl(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                int32_t k, int renorm, const float* q_scalar, const float* uniforms,
+                int32_t* n_accept, float* p_tok, float* q_tok,
+                float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
+                bool ranged, const int32_t* pos_begin, const int32_t* pos_end, int32_t gamma_max,
+                void* workspace, size_t workspace_bytes, void* stream)
 {
     if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
     const int64_t rows = (int64_t)n_draft + B;
@@ -196,13 +200,50 @@ int picospec_verify(const void* tgt_logits, int dtype, int64_t ld, int32_t V, fl
         if (!draft_tok) return PICOSPEC_EINVAL;
         if (!q_scalar && (k < 1 || !q_idx || !q_prob || !q_count || !q_mass)) return PICOSPEC_EINVAL;
     }
+    if (ranged) {
+        if (gamma_max < 0 || gamma_max > n_draft) return PICOSPEC_EINVAL;
+        if (B > 65535 || gamma_max >= (1 << 20)) return PICOSPEC_EUNSUPPORTED;   // a (gamma_max + 1) x B launch
+    }
     if (int rc = check_workspace(PICOSPEC_CALL_VERIFY, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
     hipStream_t s = (hipStream_t)stream;
-    if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s))
-        return hip_status(e);
+    const hipError_t e = ranged
+        ? launch_row_stats_range(tgt_logits, dtype, ld, V, temperature, B, gamma_max, seq_off, pos_begin, pos_end,
+                                 tgt_max, tgt_sum, tgt_lse, s)
+        : launch_row_stats(tgt_logits, dtype, ld, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s);
+    if (e != hipSuccess) return hip_status(e);
     return hip_status(launch_accept(tgt_logits, dtype, ld, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
                                     q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum,
-                                    n_accept, p_tok, q_tok, flags, s));
+                                    n_accept, p_tok, q_tok, flags, ranged ? pos_begin : nullptr,
+                                    ranged ? pos_end : nullptr, s));
+}
+
+}  // namespace
+
+int picospec_verify(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                    int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                    const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                    int32_t k, int renorm, const float* q_scalar, const float* uniforms,
+                    int32_t* n_accept, float* p_tok, float* q_tok,
+                    float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return verify_impl(tgt_logits, dtype, ld, V, temperature, B, n_draft, seq_off, draft_tok, q_idx, q_prob, q_count,
+                       q_mass, k, renorm, q_scalar, uniforms, n_accept, p_tok, q_tok, tgt_max, tgt_sum, tgt_lse, flags,
+                       false, nullptr, nullptr, 0, workspace, workspace_bytes, stream);
+}
+
+int picospec_verify_range(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                          int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                          int32_t k, int renorm, const float* q_scalar, const float* uniforms,
+                          const int32_t* pos_begin, const int32_t* pos_end, int32_t gamma_max,
+                          int32_t* n_accept, float* p_tok, float* q_tok,
+                          float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* flags,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    return verify_impl(tgt_logits, dtype, ld, V, temperature, B, n_draft, seq_off, draft_tok, q_idx, q_prob, q_count,
+                       q_mass, k, renorm, q_scalar, uniforms, n_accept, p_tok, q_tok, tgt_max, tgt_sum, tgt_lse, flags,
+                       true, pos_begin, pos_end, gamma_max, workspace, workspace_bytes, stream);
 }
 
 int picospec_sample_residual(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,

@@ -38,12 +38,19 @@ hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int3
 hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
                             float* row_max, float* row_sum, float* row_lse, hipStream_t stream);
 
+// the same for the target rows pos_begin[b]..pos_end[b] of every sequence only (nullable: 0 / gamma_b)
+hipError_t launch_row_stats_range(const void* logits, int dtype, int64_t ld, int V, float temperature, int B,
+                                  int gamma_max, const int32_t* seq_off, const int32_t* pos_begin,
+                                  const int32_t* pos_end, float* row_max, float* row_sum, float* row_lse,
+                                  hipStream_t stream);
+
 hipError_t launch_accept(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
                          int B, const int32_t* seq_off, const int32_t* draft_tok,
                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                          int k, int renorm, const float* q_scalar, const float* uniforms,
                          const float* tgt_max, const float* tgt_sum,
-                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags, hipStream_t stream);
+                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
+                         const int32_t* pos_begin, const int32_t* pos_end, hipStream_t stream);
 
 hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
                            int B, const int32_t* seq_off, const int32_t* n_accept,

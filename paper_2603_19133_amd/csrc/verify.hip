@@ -10,15 +10,14 @@ namespace {
 
 // One workgroup of THREADS threads per row, NV 16-byte vectors per thread and trip: M = max z, S = sum exp((z - M)/T), lse = M/T + ln S.
 template <bool BF16, int NV, int THREADS>
-__global__ __launch_bounds__(THREADS) void row_stats_kernel(
-    const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+__device__ __forceinline__ void row_stats_row(
+    const int64_t row, const void* __restrict__ logits, int64_t ld, int V, float inv_T,
     float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse)
 {
     __shared__ double red[2 * (THREADS / kWave)];
     constexpr int N = Vec<BF16>::N, E = NV * N, TILE = THREADS * E;
     static_assert(E <= 32, "one bit of the validity mask per element");
     const int tid = threadIdx.x;
-    const int64_t row = blockIdx.x;
     const RowView rv = row_view<BF16>(logits, ld, row, V);
     const int n_tiles = (rv.L + TILE - 1) / TILE;
     const float c = 1.4426950408889634f * inv_T;
@@ -71,6 +70,40 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(
     }
 }
 
+template <bool BF16, int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void row_stats_kernel(
+    const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+    float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse)
+{
+    row_stats_row<BF16, NV, THREADS>(blockIdx.x, logits, ld, V, inv_T, row_max, row_sum, row_lse);
+}
+
+// Clamp a range of draft positions to 0 <= begin <= end <= g; reports whether it had to.
+__device__ __forceinline__ bool clamp_range(const int32_t* pos_begin, const int32_t* pos_end, int b, int g, int& begin, int& end) {
+    const int rb = pos_begin ? pos_begin[b] : 0, re = pos_end ? pos_end[b] : g;
+    end = re < 0 ? 0 : (re > g ? g : re);
+    begin = rb < 0 ? 0 : (rb > end ? end : rb);
+    return rb != begin || re != end;
+}
+
+// The same for the target rows begin_b..end_b of every sequence only (verification of a part of the
+// draft): workgroup (t, b) of a (gamma_max + 1) x B grid takes position t of sequence b or leaves.
+template <bool BF16, int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void row_stats_range_kernel(
+    const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ pos_begin, const int32_t* __restrict__ pos_end,
+    float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse)
+{
+    const int b = blockIdx.y, t = blockIdx.x;
+    const int d0 = seq_off[b];
+    int g = seq_off[b + 1] - d0;
+    if (g < 0) g = 0;
+    int begin, end;
+    clamp_range(pos_begin, pos_end, b, g, begin, end);
+    if (t < begin || t > end) return;
+    row_stats_row<BF16, NV, THREADS>((int64_t)d0 + b + t, logits, ld, V, inv_T, row_max, row_sum, row_lse);
+}
+
 // One workgroup (16 waves) per sequence, one wave per draft position.  The wave looks the drafted
 // token up in the position's sparse record with 16-byte loads (four in flight per lane), front
 // first, and stops once it is found.
@@ -83,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
     const float* __restrict__ q_scalar, const float* __restrict__ uniforms,
     const float* __restrict__ tgt_max, const float* __restrict__ tgt_sum,
     int32_t* __restrict__ n_accept, float* __restrict__ p_tok, float* __restrict__ q_tok,
-    uint32_t* __restrict__ flags)
+    uint32_t* __restrict__ flags, const int32_t* __restrict__ pos_begin, const int32_t* __restrict__ pos_end)
 {
     __shared__ int s_first;
     __shared__ unsigned s_flags;
@@ -93,18 +126,20 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
     int g = seq_off[b + 1] - d0;
     unsigned fl = 0;
     if (g < 0) { fl |= 8u; g = 0; }
-    if (tid == 0) { s_first = g; s_flags = 0; }
+    int begin, end;                                   // the draft positions this call verifies (all of them by default)
+    if (clamp_range(pos_begin, pos_end, b, g, begin, end)) fl |= 8u;
+    if (tid == 0) { s_first = end; s_flags = 0; }
     __syncthreads();
     const int64_t t0 = (int64_t)d0 + b;
     const double cd = 1.4426950408889634 * (double)inv_T;
 
-    // every target row of the sequence must have finite statistics
-    for (int t = tid; t <= g; t += kThreads) {
+    // every target row of the range must have finite statistics
+    for (int t = begin + tid; t <= end; t += kThreads) {
         float M = tgt_max[t0 + t], S = tgt_sum[t0 + t];
         if (!(fabsf(M) < __builtin_huge_valf()) || !(S > 0.f) || !(S < __builtin_huge_valf())) fl |= 2u;
     }
 
-    for (int i = wave; i < g; i += kWaves) {
+    for (int i = begin + wave; i < end; i += kWaves) {
         const int64_t rd = (int64_t)d0 + i, rt = t0 + i;
         const int x = draft_tok[rd];
         const bool bad = x < 0 || x >= V;
@@ -183,6 +218,25 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
 
 }  // namespace
 
+hipError_t launch_row_stats_range(const void* logits, int dtype, int64_t ld, int V, float temperature, int B,
+                                  int gamma_max, const int32_t* seq_off, const int32_t* pos_begin,
+                                  const int32_t* pos_end, float* row_max, float* row_sum, float* row_lse,
+                                  hipStream_t stream)
+{
+    if (B == 0) return hipSuccess;
+    const float inv_T = 1.0f / temperature;
+    const int64_t n_rows = (int64_t)B * (gamma_max + 1);          // (an upper bound: workgroups outside the ranges leave at once)
+    const dim3 grid(gamma_max + 1, B);
+#define PICOSPEC_ROW_STATS_RANGE(BF, NVV, TH) \
+    hipLaunchKernelGGL((row_stats_range_kernel<BF, NVV, TH>), grid, dim3(TH), 0, stream, logits, ld, V, inv_T, seq_off, pos_begin, pos_end, row_max, row_sum, row_lse)
+    if (dtype != 1)           PICOSPEC_ROW_STATS_RANGE(false, 4, kThreads);
+    else if (n_rows >= 2048)  PICOSPEC_ROW_STATS_RANGE(true, 4, 256);
+    else if (n_rows >= 1024)  PICOSPEC_ROW_STATS_RANGE(true, 2, 512);
+    else                      PICOSPEC_ROW_STATS_RANGE(true, 2, kThreads);
+#undef PICOSPEC_ROW_STATS_RANGE
+    return hipGetLastError();
+}
+
 hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
                             float* row_max, float* row_sum, float* row_lse, hipStream_t stream)
 {
@@ -206,12 +260,13 @@ hipError_t launch_accept(const void* tgt_logits, int dtype, int64_t ld, int V, f
                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                          int k, int renorm, const float* q_scalar, const float* uniforms,
                          const float* tgt_max, const float* tgt_sum,
-                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags, hipStream_t stream)
+                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
+                         const int32_t* pos_begin, const int32_t* pos_end, hipStream_t stream)
 {
     if (B == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
-    if (dtype == 1) hipLaunchKernelGGL(accept_kernel<true>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
-    else            hipLaunchKernelGGL(accept_kernel<false>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags);
+    if (dtype == 1) hipLaunchKernelGGL(accept_kernel<true>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags, pos_begin, pos_end);
+    else            hipLaunchKernelGGL(accept_kernel<false>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, inv_T, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, flags, pos_begin, pos_end);
     return hipGetLastError();
 }
 

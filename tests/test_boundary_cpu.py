@@ -163,6 +163,21 @@ def test_downlink_calls_reject_misuse(B):
     assert res(outs=(None, FAKE, FAKE)) == B.EINVAL and res(T=float("nan")) == B.EINVAL
 
 
+def test_verify_range_rejects_misuse(B):
+    """Host-visible misuse of the ranged verification returns an error code before any launch."""
+    lib = B.lib
+
+    def vr(Bn=2, N=6, seq=FAKE, tok=FAKE, rec=(FAKE,) * 4, k=8, rn=1, qs=None, u=FAKE, rng=(FAKE, FAKE), gmax=4,
+           outs=(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE), T=1.0):
+        return lib.picospec_verify_range(FAKE, 0, 50, 50, T, Bn, N, seq, tok, *rec, k, rn, qs, u, *rng, gmax, *outs, None, 0, None)
+
+    assert vr(gmax=-1) == B.EINVAL and vr(gmax=7) == B.EINVAL and vr(Bn=70000, N=70000, gmax=1) == B.EUNSUPPORTED
+    assert vr(seq=None) == B.EINVAL and vr(tok=None) == B.EINVAL and vr(rn=2) == B.EINVAL and vr(u=None) == B.EINVAL
+    assert vr(rec=(FAKE, None, FAKE, FAKE)) == B.EINVAL and vr(k=0) == B.EINVAL and vr(T=0.0) == B.EINVAL
+    assert vr(outs=(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)) == B.EINVAL
+    assert vr(outs=(FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE)) == B.EINVAL
+
+
 def test_wire_calls_reject_misuse_and_report_sizes(B):
     """Host-visible misuse of the wire calls returns an error code before any launch; the size helpers give
     the paper's payload arithmetic (Section 3.3: 8 bytes per entry / per drafted token) plus the headers."""
