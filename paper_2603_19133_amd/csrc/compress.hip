@@ -675,14 +675,16 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             // key range of the sample
             const float wmax = wave_max(bm), wmin = -wave_max(-bn);
             if (lane == 0) { sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax)); sh.wkey[kW + wave] = short_key<BF16>(__float_as_uint(wmin)); }
+            const int target = optimistic ? r_opt : k;
+            const bool one_pass = optimistic && more && n0 > target;
+            if (one_pass) zero_hist(sh);         // (for the histogram below: the barrier of the key range serves it too)
             __syncthreads();
             key_hi = 0; key_lo = 0xFFFFFFFFu;
 #pragma unroll
             for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); }
             STAMP(2);
-            const int target = optimistic ? r_opt : k;
             bool have_tau = false;
-            if (optimistic && more && n0 > target) {
+            if (one_pass) {
                 // Optimistic pass: the threshold only has to be about right (the count at the end of the row
                 // decides), so one histogram pass over a linear scale of the sample's value range does: bin
                 // 0 holds the largest values.  A crowded pivot bin (a value range stretched by outliers)
@@ -692,8 +694,6 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                 if (vmax > vmin && vmin > kNegInf && vmax < __builtin_huge_valf()) {
                     const float width = (vmax - vmin) * (1.0f / (float)kBins);
                     const float scale = 1.0f / width;
-                    zero_hist(sh);
-                    __syncthreads();
 #pragma unroll
                     for (int e = 0; e < E0; ++e)
                         if (v[e] == v[e]) atomicAdd(&sh.hist[min((int)((vmax - v[e]) * scale), kBins - 1)], 1u);
@@ -740,7 +740,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
                 if (t > kNegInf) { tau = float_below(t); admit_all = false; key_lo = lo; }
             }
             if (admit_all && more) key_lo = 0;   // later sub-tiles may go below the sample's minimum
-            __syncthreads();
+            if (!have_tau) __syncthreads();      // (with a one-pass threshold the barrier behind the pivot stands here already)
             if (!optimistic) {
                 const int failed_at = append(nv0_t{}, v, tau, admit_all, tid * N - rv.o);
                 if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: the sample fits the empty buffer
