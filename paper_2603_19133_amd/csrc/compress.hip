@@ -1020,6 +1020,77 @@ __global__ __launch_bounds__(256) void sample_draft_kernel(
     }
 }
 
+// The same draw for records whose rows start on 16-byte boundaries (k a multiple of 4): the wave reads the row
+// with 16-byte loads, 1 KB per instruction, and keeps it in registers; lane l of load i owns the four slots
+// 4 * (64 i + l) ..., so a chunk of 256 slots is summed by a wave scan and the chunks by a running carry.
+template <int CHUNKS>
+__global__ __launch_bounds__(256) void sample_draft_vec_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ prob, const int32_t* __restrict__ count,
+    const float* __restrict__ mass, int k, int n_rows, const float* __restrict__ uniforms,
+    int32_t* __restrict__ tok, float* __restrict__ q_scalar)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (row >= n_rows) return;
+    const float* p = prob + row * k;
+    int cnt = count[row];
+    cnt = cnt < 0 ? 0 : (cnt > k ? k : cnt);
+    if (cnt == 0) { if (lane == 0) { tok[row] = -1; if (q_scalar) q_scalar[row] = 0.f; } return; }
+    const float4* p4 = reinterpret_cast<const float4*>(p);
+    float4 v[CHUNKS];
+    double incl[CHUNKS];                      // inclusive sum over the chunk up to and including this lane's four
+    double carry[CHUNKS + 1];                 // sum of the chunks in front
+    carry[0] = 0.0;
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const int s0 = 4 * (i * kWave + lane);
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s0 < cnt) v[i] = p4[i * kWave + lane];
+        if (s0 + 1 >= cnt) v[i].y = 0.f;      // slots behind the count carry no weight
+        if (s0 + 2 >= cnt) v[i].z = 0.f;
+        if (s0 + 3 >= cnt) v[i].w = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const double mine = (((double)v[i].x + (double)v[i].y) + (double)v[i].z) + (double)v[i].w;
+        incl[i] = wave_scan_incl(mine);
+        carry[i + 1] = carry[i] + read_lane(incl[i], kWave - 1);
+    }
+    const double target = (double)uniforms[row] * carry[CHUNKS];
+    int pick = -1;
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        if (pick < 0) {                       // (uniform across the wave)
+            const unsigned long long ball = __ballot(carry[i] + incl[i] > target);
+            if (ball) {
+                const int owner = __ffsll((long long)ball) - 1;
+                int mine_pick = -1;
+                if (lane == owner) {
+                    const double w4[4] = {(double)v[i].x, (double)v[i].y, (double)v[i].z, (double)v[i].w};
+                    double cum = carry[i] + incl[i] - ((((double)v[i].x + (double)v[i].y) + (double)v[i].z) + (double)v[i].w);
+                    mine_pick = 4 * (i * kWave + lane) + 3;
+#pragma unroll
+                    for (int e = 3; e >= 0; --e) {   // first slot of the four whose cumulative weight exceeds the target
+                        double upto = cum;
+#pragma unroll
+                        for (int f = 0; f <= e; ++f) upto += w4[f];
+                        if (upto > target) mine_pick = 4 * (i * kWave + lane) + e;
+                    }
+                }
+                pick = __shfl(mine_pick, owner, kWave);
+            }
+        }
+    }
+    if (pick < 0 || pick >= cnt) {            // rounding: the last slot with weight
+        if (lane == 0) { pick = cnt - 1; while (pick > 0 && !(p[pick] > 0.f)) --pick; }
+        pick = __shfl(pick, 0, kWave);
+    }
+    if (lane == 0) {
+        tok[row] = idx[row * k + pick];
+        if (q_scalar) q_scalar[row] = p[pick] / mass[row];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
@@ -1058,7 +1129,20 @@ hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int3
 {
     if (n_rows == 0) return hipSuccess;
     const int rows_per_block = 256 / kWave;
-    hipLaunchKernelGGL(sample_draft_kernel, dim3((n_rows + rows_per_block - 1) / rows_per_block), dim3(256), 0, stream,
+    const dim3 grid((n_rows + rows_per_block - 1) / rows_per_block);
+    if ((k & 3) == 0 && k <= 16 * 256 && (((uintptr_t)prob) & 15u) == 0) {
+        // rows on 16-byte boundaries: the row in registers, as many 256-slot chunks as k needs
+#define PICOSPEC_SAMPLE_DRAFT(C) \
+        hipLaunchKernelGGL(sample_draft_vec_kernel<C>, grid, dim3(256), 0, stream, idx, prob, count, mass, k, n_rows, uniforms, tok, q_scalar)
+        if (k <= 256)       PICOSPEC_SAMPLE_DRAFT(1);
+        else if (k <= 1024) PICOSPEC_SAMPLE_DRAFT(4);
+        else if (k <= 2048) PICOSPEC_SAMPLE_DRAFT(8);
+        else                PICOSPEC_SAMPLE_DRAFT(16);
+#undef PICOSPEC_SAMPLE_DRAFT
+        static_assert(kMaxK <= 16 * 256, "sixteen chunks hold the longest record");
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(sample_draft_kernel, grid, dim3(256), 0, stream,
                        idx, prob, count, mass, k, n_rows, uniforms, tok, q_scalar);
     return hipGetLastError();
 }

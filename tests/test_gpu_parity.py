@@ -317,6 +317,44 @@ def test_sample_draft_matches_oracle(gpu, pu, ps):
     pu.assert_close(pu.n(qs_g)[keep], want_q[keep], pu.RTOL, "q_scalar")
 
 
+@pytest.mark.parametrize("k", [1, 4, 64, 250, 256, 1000, 1024, 2048, 4096, 5000])
+def test_sample_draft_record_shapes(gpu, pu, ps, k):
+    """The draw over records of every length class (rows on and off 16-byte boundaries, one to sixteen chunks,
+    beyond the longest record the compressor writes), with ragged counts, empty rows and zero weights at the
+    end; both sides get the same fp32 record."""
+    _announce("sample_draft shapes", k)
+    rng = np.random.default_rng(k)
+    rows = 97
+    count = rng.integers(0, k + 1, rows).astype(np.int32)
+    count[:5] = [k, 0, 1, min(k, 3), max(k - 1, 0)]
+    idx = np.full((rows, k), -1, np.int32)
+    prob = np.zeros((rows, k), np.float32)
+    for r in range(rows):
+        c = count[r]
+        idx[r, :c] = rng.choice(150000, c, replace=False)
+        p = np.sort(rng.dirichlet(np.full(max(c, 1), 0.2)))[::-1][:c] * 0.9
+        prob[r, :c] = p.astype(np.float32)
+    if count[7] >= 2:
+        prob[7, count[7] // 2:count[7]] = 0.0                 # a record whose tail carries no weight
+    u = rng.random(rows, dtype=np.float32)
+    u[7] = np.float32(1.0 - 2.0 ** -24)
+    mass = prob.astype(np.float64).sum(axis=1)
+    o = oracle.Compressed(idx, prob.astype(np.float64), count, mass, None, None, k)
+    live = count > 0
+    tok_o, slot_o, mar = oracle.sample_draft(oracle.Compressed(idx[live], o.prob[live], count[live], mass[live], None, None, k), u[live])
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+    q = ps.Compressed(d(idx), d(prob), d(count), d(mass.astype(np.float32)), torch.zeros(rows, device=gpu), k)
+    tok_g, qs_g = ps.sample_draft(q, d(u))
+    torch.cuda.synchronize()
+    tg, qg = pu.n(tok_g), pu.n(qs_g)
+    assert np.all(tg[~live] == -1) and np.all(qg[~live] == 0)
+    keep = mar >= pu.CDF_MARGIN
+    assert keep.mean() > 0.9
+    assert (tg[live][keep] == tok_o[keep]).all()
+    want_q = o.prob[live][np.arange(live.sum()), slot_o] / mass[live]
+    pu.assert_close(qg[live][keep], want_q[keep], pu.RTOL, "q_scalar")
+
+
 def test_residual_empty_falls_back_to_target(gpu, pu, ps):
     _announce("residual empty")
     V = 300
