@@ -143,6 +143,11 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
         const int64_t rd = (int64_t)d0 + i, rt = t0 + i;
         const int x = draft_tok[rd];
         const bool bad = x < 0 || x >= V;
+        // everything the decision needs besides qhat is asked for now (every lane the same address), so that it
+        // arrives while the record is scanned instead of after it
+        const float M_t = tgt_max[rt], S_t = tgt_sum[rt], u_t = uniforms[rt];
+        const float z_t = bad ? 0.f : logit_at<BF16>(tgt_logits, ld, rt, x);
+        const float mass_d = (!q_scalar && renorm) ? q_mass[rd] : 1.f;
         double qh = 0.0;
         if (q_scalar) {
             qh = (double)q_scalar[rd];
@@ -188,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
             for (int o = 32; o > 0; o >>= 1) slot = max(slot, __shfl_xor(slot, o, kWave));
             if (slot >= 0 && !bad) {
                 qh = (double)q_prob[rd * k + slot];
-                if (renorm) qh /= (double)q_mass[rd];
+                if (renorm) qh /= (double)mass_d;
             } else if (lane == 0) {
                 fl |= 1u;
             }
@@ -196,11 +201,8 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(
         if (lane == 0) {
             if (bad) fl |= 8u;
             double p = 0.0;
-            if (!bad) {
-                const float z = logit_at<BF16>(tgt_logits, ld, rt, x);
-                p = exp_emit(z, tgt_max[rt], cd) / (double)tgt_sum[rt];
-            }
-            const double u = (double)uniforms[rt];
+            if (!bad) p = exp_emit(z_t, M_t, cd) / (double)S_t;
+            const double u = (double)u_t;
             // u < min(1, p/qhat), without forming the quotient; qhat = 0 counts as ratio = +inf
             const bool accept = (u < 1.0) && (qh > 0.0 ? (u * qh < p) : true);
             if (!accept) atomicMin(&s_first, i);
