@@ -274,6 +274,31 @@ def test_round_at_the_largest_vocabulary_and_record(gpu, pu, ps, dtype):
     assert e.value.code == ps.EUNSUPPORTED
 
 
+@pytest.mark.parametrize("T,spread", [(0.05, 3.0), (0.2, 8.0), (20.0, 3.0), (1.0, 40.0)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_round_at_extreme_temperatures(gpu, pu, T, spread, dtype):
+    """Very peaked (exponents of several hundred below the maximum) and nearly flat distributions: the probabilities,
+    masses and the residual draw keep their tolerances."""
+    _announce("extreme temperature", T, spread, dtype)
+    rng = np.random.default_rng(int(T * 100) + int(spread))
+    V, k = 6007, 300
+    g = np.array([3, 0, 5, 1, 4, 2], np.int32)
+    off = W.seq_offsets(g)
+    N, B = int(off[-1]), len(g)
+    tgt = (rng.standard_normal((N + B, V)) * spread).astype(np.float32)
+    draft = np.empty((N, V), np.float32)
+    for b in range(B):
+        for i in range(g[b]):
+            draft[off[b] + i] = tgt[off[b] + b + i] + rng.standard_normal(V).astype(np.float32) * spread * 0.1
+    if dtype == "bf16":
+        tgt, draft = W.to_bf16_bits(tgt), W.to_bf16_bits(draft)
+    w = W.Workload("extreme", 93, B, 0, 5, V, dtype, T, k, 0.0, 1, "custom")
+    r = _custom_round(w, draft, tgt, off, rng.random(N + B, dtype=np.float32), rng.random(N, dtype=np.float32))
+    o = pu.oracle_round(r)
+    gq = pu.gpu_round(r, o.tok, gpu)
+    pu.compare_round(gq, o, r, max_excluded_frac=0.34)
+
+
 def test_scalar_q_uplink_and_foreign_tokens(gpu, pu, ps):
     """The edge's scalar q_i replaces the sparse lookup; tokens outside the record are accepted and flagged."""
     _announce("scalar q / foreign tokens")
