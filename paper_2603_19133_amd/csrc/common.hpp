@@ -276,6 +276,70 @@ __device__ __forceinline__ void block_softmax_stats(float m, float s, float c, d
     S = tot;
 }
 
+// ---------------------------------------------------------------- streaming row statistics
+
+// One workgroup of THREADS threads per row, NV 16-byte vectors per thread and trip: M = max z, S = sum exp((z - M)/T), lse = M/T + ln S.
+template <bool BF16, int NV, int THREADS>
+__device__ __forceinline__ void row_stats_row(
+    const int64_t row, const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+    float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse)
+{
+    __shared__ double red[2 * (THREADS / kWave)];
+    constexpr int N = Vec<BF16>::N, E = NV * N, TILE = THREADS * E;
+    static_assert(E <= 32, "one bit of the validity mask per element");
+    const int tid = threadIdx.x;
+    const RowView rv = row_view<BF16>(logits, ld, row, V);
+    const int n_tiles = (rv.L + TILE - 1) / TILE;
+    const float c = 1.4426950408889634f * inv_T;
+
+    uint4 cur[NV], nxt[NV];
+    auto load_tile = [&](int it, uint4 (&dst)[NV]) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            int q = it * (THREADS * NV) + j * THREADS + tid;
+            dst[j] = make_uint4(0, 0, 0, 0);
+            if (vec_in_row<BF16>(rv, q)) dst[j] = load16_stream(rv.base + q);
+        }
+    };
+    load_tile(0, cur);
+    OnlineSum os;
+    for (int it = 0; it < n_tiles; ++it) {
+        if (it + 1 < n_tiles) load_tile(it + 1, nxt);
+        float v[E];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float t[N];
+            unpack<BF16>(cur[j], t);
+#pragma unroll
+            for (int e = 0; e < N; ++e) v[j * N + e] = t[e];
+        }
+        if (it == 0 || it == n_tiles - 1) {
+            unsigned vm = 0;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * (THREADS * NV) + j * THREADS + tid) << (j * N);
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : kNegInf;
+        }
+        float bm = v[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) bm = fmaxf(bm, v[e]);
+        const float mref = os.rebase(bm, c);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc += exp_stream(v[e], mref, c);
+        os.s += acc;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+    }
+    float M; double S;
+    block_softmax_stats<THREADS / kWave>(os.m, os.s, c, red, M, S);
+    if (tid == 0) {
+        row_max[row] = M;
+        row_sum[row] = (float)S;
+        if (row_lse) row_lse[row] = (float)((double)M * (double)inv_T + log(S));
+    }
+}
+
 // Largest float below x (x finite or +inf); -inf stays -inf.  x >= t  <=>  x > float_below(t) for non-NaN x.
 __device__ __forceinline__ float float_below(float t) {
     uint32_t b = __float_as_uint(t);

@@ -418,8 +418,10 @@ __device__ __forceinline__ int optimistic_rank(int k, int V, int m) {
     return (int)ceilf(r);
 }
 
+// One row of the compression: the workgroup that runs this writes record `row` of `n_rows`.
 template <bool BF16>
-__global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
+__device__ __forceinline__ void compress_row(
+    const int64_t row, const int n_rows,
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
     float* __restrict__ mass, float* __restrict__ lse,
@@ -439,7 +441,6 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     constexpr int RING = PICOSPEC_COMPRESS_RING * (2 / SV);  // sub-tile buffers: one in use, the others in flight
     static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int64_t row = blockIdx.x;              // row of the record written
     // Row read: the same one, or (downlink record, Section 3.3) the target row of sequence `row` at its
     // first rejected or bonus position, seq_off[b] + b + n_accept[b] (n_accept clamped to 0..gamma_b).
     int64_t in_row = row;
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     // 100 MHz wall clock at the phase boundaries, 16 words per row behind the prob array, which the caller
     // of such a build must have allocated (python -m paper_2603_19133_amd.phase_clocks does).
 #ifdef PICOSPEC_PHASE_CLOCKS
-    unsigned long long* stamp_out = reinterpret_cast<unsigned long long*>(prob + (int64_t)gridDim.x * k) + (int64_t)blockIdx.x * 16;
+    unsigned long long* stamp_out = reinterpret_cast<unsigned long long*>(prob + (int64_t)n_rows * k) + row * 16;
 #define STAMP(i) do { if (threadIdx.x == 0) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); stamp_out[i] = wall_clock64(); } } while (0)
 #else
     unsigned long long* stamp_out = nullptr;
@@ -617,25 +618,29 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
             asm volatile("" : "+v"(slot[8]), "+v"(slot[9]), "+v"(slot[10]), "+v"(slot[11]),
                          "+v"(slot[12]), "+v"(slot[13]), "+v"(slot[14]), "+v"(slot[15]));
         }
-        // addresses and ids of all columns first (every lane, back to back), then only the write under each mask
+        // eight columns at a time: their addresses and ids first (every lane, back to back), then only the write
+        // under each column's mask
         const unsigned va = val_addr;
-        unsigned at[NVV * N], id[NVV * N];
+        static_assert((NVV * N) % 8 == 0, "writes go in blocks of eight columns");
 #pragma unroll
-        for (int j = 0; j < NVV; ++j)
+        for (int i0 = 0; i0 < NVV * N; i0 += 8) {
+            unsigned at[8], id[8];
 #pragma unroll
-            for (int e = 0; e < N; ++e) {
-                at[j * N + e] = ((unsigned)slot[j * N + e] & wrap) + va;
-                id[j * N + e] = (unsigned)(x0 + j * kT * N + e);
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u;
+                at[u] = ((unsigned)slot[i] & wrap) + va;
+                id[u] = (unsigned)(x0 + (i / N) * kT * N + i % N);
             }
 #pragma unroll
-        for (int i = 0; i < NVV * N; ++i) {
-            unsigned long long saved;
-            asm volatile("s_and_saveexec_b64 %[sv], %[m]\n\t"
-                         "ds_write2st64_b32 %[at], %[x], %[id] offset1:128\n\t"
-                         "s_mov_b64 exec, %[sv]"
-                         : [sv] "=&s"(saved)
-                         : [m] "s"(passed[i]), [at] "v"(at[i]), [id] "v"(id[i]), [x] "v"(v[i])
-                         : "memory", "scc");
+            for (int u = 0; u < 8; ++u) {
+                unsigned long long saved;
+                asm volatile("s_and_saveexec_b64 %[sv], %[m]\n\t"
+                             "ds_write2st64_b32 %[at], %[x], %[id] offset1:128\n\t"
+                             "s_mov_b64 exec, %[sv]"
+                             : [sv] "=&s"(saved)
+                             : [m] "s"(passed[i0 + u]), [at] "v"(at[u]), [id] "v"(id[u]), [x] "v"(v[i0 + u])
+                             : "memory", "scc");
+            }
         }
     };
     static_assert(offsetof(CompressShared, cand_id) - offsetof(CompressShared, cand_val) == 128 * 64 * 4,
@@ -872,7 +877,7 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
     //      into the caches with ordinary loads whose data is dropped, so that row does not start by waiting
     //      for HBM.  One register quadruple takes all of them (tied operand: loads return in order).
     u32x4_t dropped = {0u, 0u, 0u, 0u};
-    if (ahead > 0 && row + ahead < (int64_t)gridDim.x) {
+    if (ahead > 0 && row + ahead < (int64_t)n_rows) {
         const RowView nv = row_view<BF16>(logits, ld, row + ahead, V);
         const int nq2 = (nv.L + N - 1) / N;
 #pragma unroll
@@ -976,6 +981,36 @@ __global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
         count[row] = (int)tc;
     }
     STAMP(15);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
+    const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
+    int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
+    float* __restrict__ mass, float* __restrict__ lse,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept, int ahead)
+{
+    compress_row<BF16>(blockIdx.x, (int)gridDim.x, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+                       seq_off, n_accept, ahead);
+}
+
+// Both streams of a small round in one launch (the draft rows' compression and the target rows' statistics do
+// not depend on each other): workgroups 0..n_draft-1 compress, the others take one target row each.
+// (For rounds of a few rows: registers are not held down to four waves per SIMD here.)
+template <bool BF16>
+__global__ __launch_bounds__(kT, 2) void round_stream_kernel(
+    const void* __restrict__ draft_logits, int64_t ld_d, int n_draft, int V, float inv_T, int k, float top_p,
+    int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
+    float* __restrict__ mass, float* __restrict__ lse,
+    const void* __restrict__ tgt_logits, int64_t ld_t,
+    float* __restrict__ tgt_max, float* __restrict__ tgt_sum, float* __restrict__ tgt_lse)
+{
+    if ((int)blockIdx.x < n_draft) {
+        compress_row<BF16>(blockIdx.x, n_draft, draft_logits, ld_d, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+                           nullptr, nullptr, 0);
+    } else {
+        row_stats_row<BF16, 2, kT>((int64_t)blockIdx.x - n_draft, tgt_logits, ld_t, V, inv_T, tgt_max, tgt_sum, tgt_lse);
+    }
 }
 
 // The drafter's draw: inverse CDF over the used slots, one wave per row.
@@ -1120,6 +1155,28 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
     const float inv_T = 1.0f / temperature;
     if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
     else       hipLaunchKernelGGL(f32, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
+    return hipGetLastError();
+}
+
+hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d, int n_draft, int V, float temperature,
+                               int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
+                               const void* tgt_logits, int64_t ld_t, int n_target,
+                               float* tgt_max, float* tgt_sum, float* tgt_lse, hipStream_t stream)
+{
+    static bool limit_raised[2][kMaxDevices] = {};
+    const size_t smem = sizeof(CompressShared);
+    auto f32 = round_stream_kernel<false>;
+    auto b16 = round_stream_kernel<true>;
+    const int which = dtype == 1;
+    {
+        int dev = 0;
+        hipError_t e = raise_lds_limit_once(which ? (const void*)b16 : (const void*)f32, smem, limit_raised[which], dev);
+        if (e != hipSuccess) return e;
+    }
+    if (n_draft + n_target == 0) return hipSuccess;
+    const float inv_T = 1.0f / temperature;
+    if (which) hipLaunchKernelGGL(b16, dim3(n_draft + n_target), dim3(kT), smem, stream, draft_logits, ld_d, n_draft, V, inv_T, k, top_p, idx, prob, count, mass, lse, tgt_logits, ld_t, tgt_max, tgt_sum, tgt_lse);
+    else       hipLaunchKernelGGL(f32, dim3(n_draft + n_target), dim3(kT), smem, stream, draft_logits, ld_d, n_draft, V, inv_T, k, top_p, idx, prob, count, mass, lse, tgt_logits, ld_t, tgt_max, tgt_sum, tgt_lse);
     return hipGetLastError();
 }
 

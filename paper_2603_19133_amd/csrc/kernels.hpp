@@ -31,6 +31,12 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
                            float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream);
 
+// the draft rows' compression and the target rows' statistics in one launch (small rounds)
+hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d, int n_draft, int V, float temperature,
+                               int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
+                               const void* tgt_logits, int64_t ld_t, int n_target,
+                               float* tgt_max, float* tgt_sum, float* tgt_lse, hipStream_t stream);
+
 hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
                                int k, int n_rows, const float* uniforms, int32_t* tok, float* q_scalar,
                                hipStream_t stream);
@@ -58,6 +64,14 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                            int k, int renorm, const float* uniforms,
                            int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
+
+// acceptance and residual draw of every sequence in one launch (small rounds)
+hipError_t launch_decide(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
+                         int B, const int32_t* seq_off, const int32_t* draft_tok,
+                         const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                         int k, int renorm, const float* uniforms, const float* tgt_max, const float* tgt_sum,
+                         int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
+                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, hipStream_t stream);
 
 hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t ld, int V, float temperature,
                                   int B, const int32_t* seq_off, const int32_t* n_accept,
