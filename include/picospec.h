@@ -9,6 +9,7 @@
  *   picospec_verify          parallel verification: acceptance test, first rejection (Section 3.3)
  *   picospec_verify_range    the same for a range of each draft's positions (Section 3.2, Fast Verification)
  *   picospec_sample_residual correction token ~ norm(max(0, P_j - Q_j)), or the bonus token
+ *   picospec_round           the three calls above as one (two launches for small rounds)
  *   picospec_row_stats / picospec_compress_rejected / picospec_resample_sparse
  *                            the paper's own downlink: Top-K record of the target row at the
  *                            rejected position, local resampling at the edge (Section 3.3, Eq. 4)
@@ -218,6 +219,27 @@ int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, in
                              int32_t k, int renorm, const float* uniforms,
                              int32_t* out_tok, float* resid_mass, uint32_t* flags,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One call for a whole round with the draft side compressed (Section 3.3): picospec_compress of the draft
+ * rows, picospec_verify with the records, picospec_sample_residual, with the same arguments, outputs and
+ * flags as the three calls (verify_flags as picospec_verify's, residual_flags as picospec_sample_residual's).
+ * The drafted tokens must be known beforehand (in a deployment they come from picospec_sample_draft on an
+ * earlier compress of the same rows; the records written here are then the same ones).
+ * Rounds of up to 512 rows (draft + target) are enqueued as two launches instead of four (the two streaming
+ * passes together, then acceptance and residual draw of a sequence in one workgroup): such rounds are bound
+ * by the launches' serial parts, not by bandwidth.  Larger rounds are the four launches of the separate calls.
+ * The records are the same bit for bit in both schedules; the target statistics of the two-launch schedule are
+ * summed in another order, so what depends on them agrees with the separate calls to rounding.
+ */
+int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, int64_t ld_draft, int64_t ld_tgt,
+                   int32_t V, float temperature, int32_t B, int32_t n_draft, const int32_t* seq_off,
+                   const int32_t* draft_tok, int32_t k, float top_p, int renorm, const float* uniforms,
+                   int32_t* q_idx, float* q_prob, int32_t* q_count, float* q_mass, float* q_lse,
+                   int32_t* n_accept, float* p_tok, float* q_tok,
+                   float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* verify_flags,
+                   int32_t* out_tok, float* resid_mass, uint32_t* residual_flags,
+                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * ---- Wire messages of a round (Section 3.3) ----------------------------------------------------

@@ -23,7 +23,7 @@ LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
 WIRE_FP32, WIRE_FP16, WIRE_BF16 = 0, 1, 2
 WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 
-EXPORTS = ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
+EXPORTS = ("picospec_round", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
            "picospec_downlink_bytes_max", "picospec_uplink_bytes",
@@ -42,6 +42,8 @@ lib.picospec_verify.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p,
                                 _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_verify_range.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int,
                                       _p, _p, _p, _p, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_round.argtypes = [_p, _p, C.c_int, _i64, _i64, _i32, _f, _i32, _i32, _p, _p, _i32, _f, C.c_int, _p,
+                               _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_sample_residual.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
                                          _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_row_stats.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _p, _p, _p, _p]
@@ -66,7 +68,7 @@ lib.picospec_strerror.restype = C.c_char_p
 for _n in ("picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse", "picospec_version",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
-           "picospec_verify_range"):
+           "picospec_verify_range", "picospec_round"):
     getattr(lib, _n).restype = C.c_int
 
 
@@ -192,6 +194,28 @@ def verify_range(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: 
                                      _ptr(out.tgt_max), _ptr(out.tgt_sum), _ptr(out.tgt_lse), _ptr(out.flags),
                                      None, 0, _stream()))
     return out
+
+
+def round(draft_logits: torch.Tensor, tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor,
+          n_draft: int, draft_tok: torch.Tensor, k: int, uniforms: torch.Tensor, top_p: float = 0.0, renorm: int = 1,
+          q: "Compressed | None" = None, ver: "Verified | None" = None, res: "Residual | None" = None):
+    """picospec_round -> (Compressed, Verified, Residual): the whole round in one call."""
+    dt, ld_d = _logits_2d(draft_logits) if n_draft else (_dtype_code(tgt_logits), V)
+    dt_t, ld_t = _logits_2d(tgt_logits)
+    if dt != dt_t:
+        raise PicoSpecError(EDTYPE)
+    B = seq_off.shape[0] - 1
+    dev = tgt_logits.device
+    q = q or alloc_compressed(n_draft, k, dev)
+    ver = ver or alloc_verified(B, n_draft, dev)
+    res = res or alloc_residual(B, dev)
+    _check(lib.picospec_round(_ptr(draft_logits), _ptr(tgt_logits), dt, ld_d, ld_t, V, temperature, B, n_draft,
+                              _ptr(seq_off), _ptr(draft_tok), k, top_p, renorm, _ptr(uniforms),
+                              _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), _ptr(q.lse),
+                              _ptr(ver.n_accept), _ptr(ver.p_tok), _ptr(ver.q_tok),
+                              _ptr(ver.tgt_max), _ptr(ver.tgt_sum), _ptr(ver.tgt_lse), _ptr(ver.flags),
+                              _ptr(res.out_tok), _ptr(res.resid_mass), _ptr(res.flags), None, 0, _stream()))
+    return q, ver, res
 
 
 @dataclass

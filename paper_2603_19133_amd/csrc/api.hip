@@ -99,6 +99,56 @@ int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, in
                                              uniforms, out_tok, resid_mass, flags, (hipStream_t)stream));
 }
 
+// ---- one call for a whole round
+
+int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, int64_t ld_draft, int64_t ld_tgt,
+                   int32_t V, float temperature, int32_t B, int32_t n_draft, const int32_t* seq_off,
+                   const int32_t* draft_tok, int32_t k, float top_p, int renorm, const float* uniforms,
+                   int32_t* q_idx, float* q_prob, int32_t* q_count, float* q_mass, float* q_lse,
+                   int32_t* n_accept, float* p_tok, float* q_tok,
+                   float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* verify_flags,
+                   int32_t* out_tok, float* resid_mass, uint32_t* residual_flags,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
+    const int64_t rows = (int64_t)n_draft + B;
+    if (rows > INT32_MAX) return PICOSPEC_EINVAL;
+    if (int rc = check_logits(draft_logits, dtype, ld_draft, n_draft, V, temperature)) return rc;
+    if (int rc = check_logits(tgt_logits, dtype, ld_tgt, rows, V, temperature)) return rc;
+    if (k < 1 || k > V || std::isnan(top_p) || (renorm != 0 && renorm != 1)) return PICOSPEC_EINVAL;
+    if (k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (n_draft > 0 && (!draft_tok || !q_idx || !q_prob || !q_count || !q_mass || !q_lse)) return PICOSPEC_EINVAL;
+    if (B > 0 && (!seq_off || !uniforms || !n_accept || !verify_flags || !tgt_max || !tgt_sum || !out_tok ||
+                  !resid_mass || !residual_flags)) return PICOSPEC_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    // A round that leaves most of the chip idle is bound by the serial part of each launch: the two streaming
+    // kernels go out as one and the two per-sequence kernels as one.  A round that fills the chip is not: the
+    // four launches of the separate calls are the faster schedule there.
+    const bool small = rows + n_draft <= kRoundSmallRows;
+    if (small) {
+        if (hipError_t e = launch_round_stream(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx,
+                                               q_prob, q_count, q_mass, q_lse, tgt_logits, ld_tgt, (int)rows,
+                                               tgt_max, tgt_sum, tgt_lse, s))
+            return hip_status(e);
+        return hip_status(launch_decide(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
+                                        q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
+                                        verify_flags, out_tok, resid_mass, residual_flags, s));
+    }
+    if (hipError_t e = launch_compress(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx, q_prob,
+                                       q_count, q_mass, q_lse, nullptr, nullptr, s))
+        return hip_status(e);
+    if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld_tgt, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s))
+        return hip_status(e);
+    if (hipError_t e = launch_accept(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
+                                     q_count, q_mass, k, renorm, nullptr, uniforms, tgt_max, tgt_sum, n_accept, p_tok,
+                                     q_tok, verify_flags, nullptr, nullptr, s))
+        return hip_status(e);
+    return hip_status(launch_residual(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, n_accept, tgt_max, tgt_sum,
+                                      q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass,
+                                      residual_flags, s));
+}
+
 // ---- wire messages
 
 namespace {

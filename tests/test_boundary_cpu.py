@@ -178,6 +178,34 @@ def test_verify_range_rejects_misuse(B):
     assert vr(outs=(FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE)) == B.EINVAL
 
 
+def test_round_rejects_misuse(B):
+    """The one-call round checks everything the three calls it stands for check, before any launch."""
+    lib = B.lib
+
+    def rd(draft=FAKE, tgt=FAKE, dt=0, ldd=50, ldt=50, V=50, T=1.0, Bn=2, N=6, seq=FAKE, tok=FAKE, k=8, tp=0.0, rn=1,
+           u=FAKE, rec=(FAKE,) * 5, ver=(FAKE,) * 7, res=(FAKE,) * 3):
+        return lib.picospec_round(draft, tgt, dt, ldd, ldt, V, T, Bn, N, seq, tok, k, tp, rn, u, *rec, *ver, *res, None, 0, None)
+
+    assert rd(draft=None) == B.EINVAL and rd(tgt=None) == B.EINVAL and rd(dt=3) == B.EDTYPE
+    assert rd(ldd=49) == B.EINVAL and rd(ldt=49) == B.EINVAL and rd(V=0) == B.EINVAL
+    assert rd(T=0.0) == B.EINVAL and rd(T=float("nan")) == B.EINVAL and rd(Bn=-1) == B.EINVAL and rd(N=-1) == B.EINVAL
+    assert rd(seq=None) == B.EINVAL and rd(tok=None) == B.EINVAL and rd(u=None) == B.EINVAL and rd(rn=2) == B.EINVAL
+    assert rd(k=0) == B.EINVAL and rd(k=51) == B.EINVAL and rd(tp=float("nan")) == B.EINVAL
+    assert rd(V=10000, ldd=10000, ldt=10000, k=5000) == B.EUNSUPPORTED
+    for i in range(5):
+        rec = [FAKE] * 5
+        rec[i] = None
+        assert rd(rec=tuple(rec)) == B.EINVAL
+    for i in (0, 3, 4, 6):                           # n_accept, tgt_max, tgt_sum, verify_flags are required
+        ver = [FAKE] * 7
+        ver[i] = None
+        assert rd(ver=tuple(ver)) == B.EINVAL
+    for i in (0, 2):                                 # out_tok and residual_flags are required
+        res = [FAKE] * 3
+        res[i] = None
+        assert rd(res=tuple(res)) == B.EINVAL
+
+
 def test_wire_calls_reject_misuse_and_report_sizes(B):
     """Host-visible misuse of the wire calls returns an error code before any launch; the size helpers give
     the paper's payload arithmetic (Section 3.3: 8 bytes per entry / per drafted token) plus the headers."""

@@ -1,0 +1,83 @@
+"""GPU parity of picospec_round (the three calls of a round as one; two launches for small rounds, Section 3.3)
+against the oracle and, bit for bit, against the separate calls."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_19133_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ps():
+    from paper_2603_19133_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def pu():
+    import parity_util
+    return parity_util
+
+
+def _announce(*a):
+    print("[case]", *a, flush=True)
+
+
+CASES = [("cfg1", {}, 0), ("cfg2", {}, 0), ("cfg3", {"B": 6}, 0), ("cfg3", {"B": 40}, 0), ("cfg5", {"B": 10}, 0),
+         ("cfg5", {"B": 70, "V": 20011, "k": 512}, 1), ("cfg4", {"B": 3}, 0)]
+
+
+@pytest.mark.parametrize("name,scale,rnd", CASES)
+@pytest.mark.parametrize("renorm", [1, 0])
+def test_round_call_matches_oracle_and_separate_calls(gpu, pu, ps, name, scale, rnd, renorm):
+    _announce("picospec_round", name, scale, rnd, renorm)
+    w = W.WORKLOADS[name].scaled(**scale) if scale else W.WORKLOADS[name]
+    r = W.build_round(w, rnd)
+    o = pu.oracle_round(r, renorm=renorm)
+    sep = pu.gpu_round(r, o.tok, gpu, renorm=renorm)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+    q, ver, res = ps.round(pu.to_device(r.draft_logits, gpu), pu.to_device(r.tgt_logits, gpu), w.V, w.T, d(r.seq_off),
+                           r.N, d(o.tok), w.k, d(r.uniforms), top_p=w.top_p, renorm=renorm)
+    torch.cuda.synchronize()
+    one = pu.GpuRound(q, ver, res)
+    pu.compare_round(one, o, r, max_excluded_frac=0.34)
+    # the records come from the same code: bit for bit; the target statistics of the two-launch schedule are summed by
+    # 512 threads instead of 1024, so everything behind them agrees to rounding and the decisions wherever the oracle
+    # does not call them knife-edge
+    for a, b in ((q.idx, sep.q.idx), (q.prob, sep.q.prob), (q.count, sep.q.count), (q.mass, sep.q.mass), (q.lse, sep.q.lse)):
+        assert torch.equal(a, b)
+    for a, b, what in ((ver.p_tok, sep.ver.p_tok, "p_tok"), (ver.q_tok, sep.ver.q_tok, "q_tok"), (ver.tgt_sum, sep.ver.tgt_sum, "tgt_sum"),
+                       (ver.tgt_lse, sep.ver.tgt_lse, "tgt_lse")):
+        pu.assert_close(pu.n(a), pu.n(b).astype(np.float64), 2e-6, what, atol=1e-37)
+    assert torch.equal(ver.tgt_max, sep.ver.tgt_max) and torch.equal(ver.flags, sep.ver.flags)
+    off = r.seq_off
+    clear = np.array([o.ver.margin[off[b]:off[b + 1]].min(initial=np.inf) >= pu.ACCEPT_MARGIN for b in range(r.B)])
+    assert np.array_equal(pu.n(ver.n_accept)[clear], pu.n(sep.ver.n_accept)[clear])
+    same_row = pu.n(ver.n_accept) == pu.n(sep.ver.n_accept)
+    pu.assert_close(pu.n(res.resid_mass)[same_row], pu.n(sep.res.resid_mass)[same_row].astype(np.float64), 1e-5, "resid_mass", atol=1e-30)
+    sure = clear & same_row & (o.res.cdf_margin >= pu.CDF_MARGIN)
+    assert np.array_equal(pu.n(res.out_tok)[sure], pu.n(sep.res.out_tok)[sure])
+
+
+def test_round_call_empty_and_misuse(gpu, ps):
+    _announce("picospec_round empty")
+    V = 64
+    z = torch.zeros((0, V), device=gpu)
+    off = torch.zeros(1, dtype=torch.int32, device=gpu)
+    q, ver, res = ps.round(z, z, V, 1.0, off, 0, torch.zeros(0, dtype=torch.int32, device=gpu), 8, torch.zeros(0, device=gpu))
+    torch.cuda.synchronize()
+    assert q.idx.shape == (0, 8) and ver.n_accept.numel() == 0 and res.out_tok.numel() == 0
+    # a sequence without draft positions: only its bonus token
+    tgt = torch.randn((1, V), device=gpu)
+    off = torch.tensor([0, 0], dtype=torch.int32, device=gpu)
+    q, ver, res = ps.round(z, tgt, V, 1.0, off, 0, torch.zeros(0, dtype=torch.int32, device=gpu), 8, torch.full((1,), 0.5, device=gpu))
+    torch.cuda.synchronize()
+    assert int(ver.n_accept.item()) == 0 and 0 <= int(res.out_tok.item()) < V
+    with pytest.raises(ps.PicoSpecError):
+        ps.round(z, tgt, V, 1.0, off, 0, torch.zeros(0, dtype=torch.int32, device=gpu), 0, torch.full((1,), 0.5, device=gpu))
+    with pytest.raises(ps.PicoSpecError):
+        ps.round(z, tgt.to(torch.bfloat16), V, 1.0, off, 0, torch.zeros(0, dtype=torch.int32, device=gpu), 8,
+                 torch.full((1,), 0.5, device=gpu), renorm=3)
