@@ -226,9 +226,10 @@ int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, in
  * flags as the three calls (verify_flags as picospec_verify's, residual_flags as picospec_sample_residual's).
  * The drafted tokens must be known beforehand (in a deployment they come from picospec_sample_draft on an
  * earlier compress of the same rows; the records written here are then the same ones).
- * Rounds of up to 512 rows (draft + target) are enqueued as two launches instead of four (the two streaming
- * passes together, then acceptance and residual draw of a sequence in one workgroup): such rounds are bound
- * by the launches' serial parts, not by bandwidth.  Larger rounds are the four launches of the separate calls.
+ * Acceptance and residual draw of a sequence run in one workgroup (one launch, the rejected position never
+ * leaves it).  Rounds of up to 512 rows (draft + target) also stream the draft and the target rows in one
+ * launch (two launches in all instead of four): such rounds are bound by the launches' serial parts, not by
+ * bandwidth.  Larger rounds keep the two streaming launches of the separate calls (three in all).
  * The records are the same bit for bit in both schedules; the target statistics of the two-launch schedule are
  * summed in another order, so what depends on them agrees with the separate calls to rounding.
  */

@@ -122,31 +122,25 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
     if (B > 0 && (!seq_off || !uniforms || !n_accept || !verify_flags || !tgt_max || !tgt_sum || !out_tok ||
                   !resid_mass || !residual_flags)) return PICOSPEC_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    // A round that leaves most of the chip idle is bound by the serial part of each launch: the two streaming
-    // kernels go out as one and the two per-sequence kernels as one.  A round that fills the chip is not: the
-    // four launches of the separate calls are the faster schedule there.
-    const bool small = rows + n_draft <= kRoundSmallRows;
-    if (small) {
+    // The two per-sequence kernels always go out as one (the position found by the acceptance test never leaves
+    // the workgroup).  A round that leaves most of the chip idle is bound by the serial part of each launch, so
+    // its two streaming kernels go out as one as well; a round that fills the chip streams faster with each
+    // kernel in its own launch shape.
+    if (rows + n_draft <= kRoundSmallRows) {
         if (hipError_t e = launch_round_stream(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx,
                                                q_prob, q_count, q_mass, q_lse, tgt_logits, ld_tgt, (int)rows,
                                                tgt_max, tgt_sum, tgt_lse, s))
             return hip_status(e);
-        return hip_status(launch_decide(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
-                                        q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
-                                        verify_flags, out_tok, resid_mass, residual_flags, s));
+    } else {
+        if (hipError_t e = launch_compress(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx, q_prob,
+                                           q_count, q_mass, q_lse, nullptr, nullptr, s))
+            return hip_status(e);
+        if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld_tgt, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s))
+            return hip_status(e);
     }
-    if (hipError_t e = launch_compress(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx, q_prob,
-                                       q_count, q_mass, q_lse, nullptr, nullptr, s))
-        return hip_status(e);
-    if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld_tgt, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s))
-        return hip_status(e);
-    if (hipError_t e = launch_accept(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
-                                     q_count, q_mass, k, renorm, nullptr, uniforms, tgt_max, tgt_sum, n_accept, p_tok,
-                                     q_tok, verify_flags, nullptr, nullptr, s))
-        return hip_status(e);
-    return hip_status(launch_residual(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, n_accept, tgt_max, tgt_sum,
-                                      q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass,
-                                      residual_flags, s));
+    return hip_status(launch_decide(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
+                                    q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
+                                    verify_flags, out_tok, resid_mass, residual_flags, s));
 }
 
 // ---- wire messages

@@ -9,7 +9,9 @@ namespace picospec {
 
 constexpr int kMaxK = 4096;          // candidate buffer in LDS holds 16384 entries; k beyond this is refused
 constexpr int kMaxV = 1 << 20;
-constexpr int kRoundSmallRows = 512;  // picospec_round: draft + target rows up to which the two-launch schedule is used (the chip holds 512 compress workgroups)       // residual sampler keeps one partial sum per 256/512-element segment in LDS
+// picospec_round: draft + target rows up to which the two-launch schedule is used (the chip holds 512 compress
+// workgroups at a time; beyond that the separate kernels, each with its own launch shape, are as fast or faster)
+constexpr int kRoundSmallRows = 512;
 
 // Kernels whose dynamic LDS exceeds the 64 KB default need their limit raised once per device and kernel.
 // `done` is the caller's per-device record for that kernel; the current device's ordinal comes back in `dev`.
