@@ -5,7 +5,7 @@ norm(max(0, P_j - Q_j)) and the one the edge can form from the K-entry record of
 the record's values used as sent (renorm 0) and renormalised by their mass (renorm 1); and what 16-bit
 probabilities on the wire cost on top: the total variation between the edge's draw from the received record and
 from the fp32 record, and the change of the acceptance probabilities when the uplinked q_i are quantised.
-Test infrastructure: run as ``python -m oracle.downlink_bias``; prints tables (the figures quoted in the design doc)."""
+Test infrastructure: run as ``python -m oracle.downlink_bias``; prints tables of the sparse downlink's bias."""
 from __future__ import annotations
 
 import sys
