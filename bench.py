@@ -121,6 +121,8 @@ def main() -> int:
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
     compress_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    # per-step times from the same events (start of compress to start of the next step's compress)
+    step_ms = np.array([events[i][0].elapsed_time(events[i + 1][0]) for i in range(args.steps - 1)]) if args.steps > 1 else np.array([ms_step])
 
     # After it, outside the timed region: a few more steps with events between all calls, for the per-call figures.
     n_bd = max(1, min(args.steps, 10))
@@ -146,6 +148,7 @@ def main() -> int:
                    "parallelism": "1 GPU"},
         "round_algorithmic_GBps": alg["total"] / (ms_step * 1e-3) / 1e9,
         "round_frac_of_hbm_peak": alg["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_ms": {"median": float(np.median(step_ms)), "min": float(step_ms.min()), "max": float(step_ms.max())},
         "compress_ms": compress_ms,
         "call_ms": {"compress": float(call_ms[0]), "verify": float(call_ms[1]), "sample_residual": float(call_ms[2]),
                     "note": f"{n_bd} extra steps after the timed region, events between all calls"},
@@ -160,7 +163,7 @@ def main() -> int:
     }
 
     # the CPU oracle, as it stands, on a bounded sample of the same workload
-    n_cpu = args.cpu_seqs if args.cpu_seqs >= 0 else min(B, 128)
+    n_cpu = args.cpu_seqs if args.cpu_seqs >= 0 else min(B, 256)
     if n_cpu > 0:
         import oracle
         sub = W.build_round(w, 0, seqs=range(n_cpu))
