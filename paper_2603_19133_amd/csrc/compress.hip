@@ -414,7 +414,7 @@ __device__ __forceinline__ int optimistic_rank(int k, int V, int m) {
     const float r0 = (float)k * (float)m / (float)V;                  // expected rank of the row's k-th value in the tile
     const float r = r0 + 4.5f * sqrtf(r0) + 20.25f;
     const float expected = r * (float)V / (float)m;                   // candidates at the end of the row
-    if (r >= (float)k || expected > 0.8f * (float)kCap) return 0;
+    if (expected > 0.8f * (float)kCap) return 0;                      // (r may exceed k: a short record still takes the fast pass)
     return (int)ceilf(r);
 }
 

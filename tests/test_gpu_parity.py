@@ -64,7 +64,8 @@ def _compress_case(pu, ps, gpu, z, V, T, k, top_p=0.0, dtype="f32"):
 
 
 @pytest.mark.parametrize("V,k", [(1, 1), (8, 8), (8, 3), (63, 1), (1000, 1000), (4096, 4096), (5000, 4096),
-                                 (16384, 64), (16385, 64), (32769, 500), (70001, 4096)])
+                                 (16384, 64), (16385, 64), (32769, 500), (70001, 4096),
+                                 (151936, 10), (128256, 1), (40000, 3), (9000, 10), (8193, 30)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_compress_sizes_and_tails(gpu, pu, ps, V, k, dtype):
     _announce("compress sizes", V, k, dtype)
