@@ -5,18 +5,21 @@
 // Streaming selection.  A row is read with buffer loads (descriptor base + scalar offset + one
 // constant per-lane offset) in sub-tiles of two 16-byte vectors per thread through a ring of four
 // register buffers (three sub-tiles in flight behind the one being processed).
-//   * The first 8192 elements (the sample) stay in registers while a two-pass radix histogram over
-//     their order-preserving logit keys finds a threshold: a value with at least r of the sample's
-//     elements at or above it.
-//   * Optimistic pass: r is chosen so that about k + 4.5 sqrt(k) + 20 elements of the whole row are
-//     expected at or above the threshold (for exchangeable rows).  Every element of the row at
-//     or above it -- the sample included -- claims a slot of the candidate buffer in LDS with an
-//     atomic of its own and writes (value, id) there; the softmax arithmetic sits between claim and
-//     write.  If the row ends with at least k candidates that fit the buffer, the exact top k is
-//     among them, because nothing at or above the threshold was dropped.  Waves run free in this
-//     pass; too many or too few candidates give the pass up.
+//   * A sample of 8192 elements stays in registers while a histogram over their values (one pass on a
+//     linear scale, else two radix passes over the order-preserving keys) finds a threshold: a value
+//     with at least r of the sample's elements at or above it.
+//   * Optimistic pass: the sample is 256 runs of 128 bytes spread evenly over the row (logits trend with
+//     the vocabulary id, so the head of a row would misplace the threshold); it is only looked at.  r is
+//     chosen so that about k + 4.5 sqrt(k) + 20 elements of the whole row are expected at or above the
+//     threshold.  The row is then streamed from its start: every element at or above the threshold
+//     claims a slot of the candidate buffer in LDS with an atomic of its own and writes (value, id)
+//     there; the softmax arithmetic sits between claim and write.  If the row ends with at least k
+//     candidates that fit the buffer, the exact top k is among them, because nothing at or above the
+//     threshold was dropped.  Waves run free in this pass; too many or too few candidates give the
+//     pass up.
 //   * Safe pass (only after a failed optimistic pass, or when the optimistic rank would not pay):
-//     r = k, so the threshold is at or below the k-th largest of the sample.  The waves meet after
+//     the sample is the row's first 8192 elements, which are kept as candidates, and r = k, so the
+//     threshold is at or below the k-th largest of the sample.  The waves meet after
 //     every sub-tile; when the buffer is full it is pruned to the exact top k of everything seen,
 //     and from then on an element must be strictly larger than the k-th (rows are streamed in
 //     ascending id, so equal logits that come later lose the tie).
@@ -429,8 +432,8 @@ __device__ __forceinline__ void compress_row(
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
-    // A row is streamed in sub-tiles of SV 16-byte vectors per thread.  The first T0 sub-tiles (8192
-    // elements) form the sample from which the threshold is taken; they are processed together.
+    // A row is streamed in sub-tiles of SV 16-byte vectors per thread.  The sample from which the first
+    // threshold is taken has the size of T0 sub-tiles (8192 elements) and is processed in one piece.
     constexpr int N = Vec<BF16>::N;
     constexpr int SAMPLE = 8192;
     constexpr int SV = (2 * kT * N <= SAMPLE) ? 2 : 1, ES = SV * N, SUB = kT * ES;
@@ -494,6 +497,36 @@ __device__ __forceinline__ void compress_row(
             for (int j = 0; j < NVV; ++j) vm |= vec_valid_mask<BF16>(rv, q0 + j * kT) << (j * N);
 #pragma unroll
             for (int e = 0; e < NVV * N; ++e) v[e] = (vm >> e) & 1u ? v[e] : qnan;
+        }
+    };
+    // The sample that places the optimistic pass's threshold: E0 elements per thread, taken from PIECES runs of
+    // 128 bytes spread evenly over the row.  (Logits trend with the vocabulary id - frequent tokens sit at low
+    // ids - so the head of a row alone misplaces the threshold and loses the pass.)  The sample is only looked
+    // at; its elements are streamed again with the rest of the row, so these loads are ordinary, cached ones.
+    constexpr int PIECES = NV0 * (kT / 8);
+    // vector of thread tid in run j*(kT/8) + tid/8 of a row of n_vec vectors at `base`: the runs start on 128-byte
+    // lines of memory (one line fetched per run), at least 8 vectors apart once n_vec >= 8*PIECES + 8
+    auto sample_vec_of = [&](int j, int n_vec, const uint4* base) {
+        const int shift = (int)(((uintptr_t)base >> 4) & 7u);
+        const int a = ((j * (kT / 8) + (tid >> 3)) * (n_vec - 16)) / (PIECES - 1) + shift;
+        return ((a + 7) & ~7) - shift + (tid & 7);
+    };
+    auto sample_vec = [&](int j) { return sample_vec_of(j, nq, rv.base); };
+    auto load_sample = [&](uint4* dst) {
+#pragma unroll
+        for (int j = 0; j < NV0; ++j) {
+            const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(row_rsrc, sample_vec(j) * 16, 0, 0);
+            dst[j] = make_uint4(t.x, t.y, t.z, t.w);
+        }
+    };
+    auto unpack_sample = [&](const uint4* src, float* v) {      // elements outside the row become NaN
+#pragma unroll
+        for (int j = 0; j < NV0; ++j) {
+            float t[N];
+            unpack<BF16>(src[j], t);
+            const unsigned vm = vec_valid_mask<BF16>(rv, sample_vec(j));
+#pragma unroll
+            for (int e = 0; e < N; ++e) v[j * N + e] = (vm >> e) & 1u ? t[e] : qnan;
         }
     };
     // Running softmax sum of this thread: s = sum 2^(v*c - r) with an integer reference exponent
@@ -647,8 +680,7 @@ __device__ __forceinline__ void compress_row(
                   "ds_write2st64 offset1:128 reaches cand_id from cand_val");
 
     const bool more = n_sub > T0;                // the row goes on behind the sample
-    const int n0 = min(V, SAMPLE - rv.o);        // row elements in the sample
-    const int r_opt = more ? optimistic_rank(k, V, n0) : 0;
+    const int r_opt = more ? optimistic_rank(k, V, SAMPLE) : 0;
     float M = kNegInf;
     double S = 0.0;
     uint32_t key_lo = 0, key_hi = 0;
@@ -662,18 +694,37 @@ __device__ __forceinline__ void compress_row(
             for (int e = 0; e < 3; ++e) { sh.epoch_overflow[e] = 0; sh.epoch_valid[e] = 0x7FFFFFFF; }
         }
         os.mx = kNegInf; os.r = kNegInf; os.s = 0.f;
+        // Sub-tile buffers.  Optimistic pass: the first T0 take the spread sample, the others the row's first
+        // sub-tiles (sub-tile s lives in buffer (T0 + s) % RING).  Safe pass: the row's first T0 sub-tiles are
+        // the sample and are kept as candidates.
         uint4 rb[RING][SV];
+        if (optimistic) {
+            load_sample(&rb[0][0]);
 #pragma unroll
-        for (int t = 0; t < RING; ++t) load_sub(t, rb[t]);
+            for (int t = T0; t < RING; ++t) load_sub(t - T0, rb[t]);
+        } else {
+#pragma unroll
+            for (int t = 0; t < RING; ++t) load_sub(t, rb[t]);
+        }
+        const int n0 = optimistic ? SAMPLE : min(V, SAMPLE - rv.o);   // row elements in the sample
 
-        // ---- the sample: statistics and the first threshold
+        // ---- the sample: the first threshold (and, in the safe pass, the statistics of its elements)
         float tau = kNegInf;                     // elements are admitted iff > tau ...
         bool admit_all = true;                   // ... or, before a threshold exists, all of them
         {
             float v[E0];
-            unpack_vecs(nv0_t{}, tid, &rb[0][0], v, true);
-            STAMP(1);
-            const float bm = add_stats(e0_t{}, v, true);
+            float bm;
+            if (optimistic) {
+                unpack_sample(&rb[0][0], v);
+                STAMP(1);
+                bm = kNegInf;
+#pragma unroll
+                for (int e = 0; e < E0; ++e) bm = fmaxf(bm, v[e]);      // fmaxf skips the NaN of masked elements
+            } else {
+                unpack_vecs(nv0_t{}, tid, &rb[0][0], v, true);
+                STAMP(1);
+                bm = add_stats(e0_t{}, v, true);
+            }
             float bn = __builtin_huge_valf();
 #pragma unroll
             for (int e = 0; e < E0; ++e) bn = fminf(bn, v[e]);
@@ -749,24 +800,19 @@ __device__ __forceinline__ void compress_row(
             if (!optimistic) {
                 const int failed_at = append(nv0_t{}, v, tau, admit_all, tid * N - rv.o);
                 if (failed_at >= 0 && lane == 0) sh.overflowed = 1;   // cannot happen: the sample fits the empty buffer
-            } else if (!admit_all) {
-                int slot[E0];
-                unsigned long long passed[E0];
-                claim_asm(e0_t{}, v, tau, slot, passed);
-                put_asm(nv0_t{}, v, slot, passed, tid * N - rv.o);
             }
         }
 
         STAMP(4);
         bool enough = true;
         if (optimistic) {
-            // ---- behind the sample, optimistic: waves run free; a reservation that does not fit gives the
+            // ---- the row from its start, optimistic: waves run free; a reservation that does not fit gives the
             //      pass up.  The ring buffers rotate by role (no copies): while one sub-tile is processed
             //      three are in flight; loads behind the row are clamped, so they need no guard.
             const bool applies = !admit_all;     // a sample without a threshold (rows of -inf) leaves the row to the safe pass
             if (applies) {
 #pragma unroll
-                for (int t = 0; t < T0; ++t) load_sub(RING + t, rb[t]);
+                for (int t = 0; t < T0; ++t) load_sub(RING - T0 + t, rb[t]);
                 auto full = [&](int sub, uint4 (&buf)[SV]) {        // a sub-tile wholly inside the row
                     float v[ES];
                     int slot[ES];
@@ -789,14 +835,24 @@ __device__ __forceinline__ void compress_row(
                         put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     }
                 };
+                {   // sub-tile 0 may begin in front of the row (rows off the 16-byte boundary): masked like an edge
+                    float v[ES];
+                    int slot[ES];
+                    unsigned long long passed[ES];
+                    unpack_vecs(sv_t{}, tid, rb[T0], v, true);
+                    claim_asm(es_t{}, v, tau, slot, passed);
+                    add_stats(es_t{}, v, true);
+                    put_asm(sv_t{}, v, slot, passed, tid * N - rv.o);
+                    load_sub(RING, rb[T0]);
+                }
                 // the hot loop holds nothing but the common case, RING times (one copy per buffer role)
-                int sub = T0;
+                int sub = 1;
                 for (; sub + RING < n_sub; sub += RING) {
 #pragma unroll
-                    for (int r = 0; r < RING; ++r) full(sub + r, rb[(T0 + r) % RING]);
+                    for (int r = 0; r < RING; ++r) full(sub + r, rb[(T0 + 1 + r) % RING]);
                 }
 #pragma unroll
-                for (int r = 0; r < RING; ++r) ragged(sub + r, rb[(T0 + r) % RING]);
+                for (int r = 0; r < RING; ++r) ragged(sub + r, rb[(T0 + 1 + r) % RING]);
             }
             __syncthreads();
             const int held = sh.cnt >> 2;        // (this pass counts bytes of cand_val)
@@ -875,14 +931,17 @@ __device__ __forceinline__ void compress_row(
     // ---- While this row is ordered and emitted, the first sub-tiles of the row that will take a slot like
     //      this one next (`ahead` rows further: as many rows as the chip holds at a time, same XCD) are pulled
     //      into the caches with ordinary loads whose data is dropped, so that row does not start by waiting
-    //      for HBM.  One register quadruple takes all of them (tied operand: loads return in order).
+    //      for HBM: what its first loads will ask for, i.e. its spread sample (if it takes the optimistic pass)
+    //      and the sub-tiles behind it.  One register quadruple takes all of them (tied operand: loads return in order).
     u32x4_t dropped = {0u, 0u, 0u, 0u};
     if (ahead > 0 && row + ahead < (int64_t)n_rows) {
         const RowView nv = row_view<BF16>(logits, ld, row + ahead, V);
         const int nq2 = (nv.L + N - 1) / N;
+        const int n_spread = (r_opt > 0 && nq2 >= 8 * PIECES + 8) ? NV0 : 0;
 #pragma unroll
         for (int j = 0; j < RING * SV; ++j) {
-            const uint4* p = nv.base + min(j * kT + tid, nq2 - 1);
+            const int q = j < n_spread ? sample_vec_of(j, nq2, nv.base) : (j - n_spread) * kT + tid;
+            const uint4* p = nv.base + min(q, nq2 - 1);
             asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(dropped) : "v"(p));
         }
     }

@@ -75,7 +75,8 @@ def test_compress_sizes_and_tails(gpu, pu, ps, V, k, dtype):
 
 
 @pytest.mark.parametrize("pattern", ["ties", "all_equal", "ascending", "descending", "neg_inf", "signed_zero",
-                                     "two_values", "sawtooth"])
+                                     "two_values", "sawtooth", "trend_down", "trend_up", "head_hot", "head_cold",
+                                     "hot_cluster", "period_of_the_sample"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
     _announce("compress adversarial", pattern, dtype)
@@ -96,8 +97,17 @@ def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
         z[:, ::97] = -1.0
     elif pattern == "two_values":
         z = np.where(rng.random((3, V)) < 0.01, 2.0, -2.0).astype(np.float32)
-    else:
+    elif pattern == "sawtooth":
         z = np.tile((np.arange(V) % 1000).astype(np.float32) * 0.01, (3, 1))
+    else:
+        # values that depend on the vocabulary id, as logits do (frequent tokens sit at low ids): the threshold
+        # comes from a sample spread over the row, and whatever the sample misses the count at the row's end catches
+        ids = np.arange(V, dtype=np.float64)
+        bias = {"trend_down": -9.0 * ids / V, "trend_up": 9.0 * ids / V,
+                "head_hot": np.where(ids < 8192, 6.0, 0.0), "head_cold": np.where(ids < 8192, -6.0, 0.0),
+                "hot_cluster": np.where((ids > 20000) & (ids < 20600), 9.0, 0.0),       # between the sample's runs or on them
+                "period_of_the_sample": 4.0 * np.cos(2 * np.pi * ids * 256 / V)}[pattern]
+        z = (rng.standard_normal((3, V)) * 3 + bias).astype(np.float32)
     _compress_case(pu, ps, gpu, z, V, 1.3, k, dtype=dtype)
 
 
