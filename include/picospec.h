@@ -40,6 +40,10 @@
  *     Data-dependent conditions never fail a call; they set bits in `flags`.
  *   - Thread safety: no global mutable state besides per-device kernel attributes set on first
  *     use; concurrent calls on different streams are independent.
+ *   - Stream capture: a call only enqueues kernels (no memset, no copy, no allocation, no
+ *     synchronisation), so a stream that is being captured into a HIP graph records it like any
+ *     other launch.  The kernel attributes are set the first time a kernel is used on a device:
+ *     make each call once outside a capture first.
  */
 #ifndef PICOSPEC_H
 #define PICOSPEC_H
