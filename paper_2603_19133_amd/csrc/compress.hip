@@ -107,18 +107,20 @@ __device__ __forceinline__ void zero_hist(CompressShared& sh) {
 
 // Scan the kBins counters in sh.hist (each thread owning kBinsPer consecutive bins) and find the
 // bin in which the running count first reaches `need`.  Broadcasts its index, the count in front of
-// it and its own count through sh.piv_*.  Returns nothing; read sh.piv_* after the call.
-__device__ __forceinline__ void find_pivot_bin(CompressShared& sh, int need) {
+// it and its own count through sh.piv_*; read them after the call.  Returns the total count.  A histogram
+// that holds fewer than `need` has no such bin: the last bin is reported then, with the count 0.
+__device__ __forceinline__ int find_pivot_bin(CompressShared& sh, int need) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     int h[kBinsPer], loc = 0;
 #pragma unroll
     for (int j = 0; j < kBinsPer; ++j) { h[j] = (int)sh.hist[tid * kBinsPer + j]; loc += h[j]; }
     const int incl = wave_scan_incl(loc);
     if (lane == kWave - 1) sh.wtot[wave] = incl;
+    if (tid == 0) { sh.piv_bin = kBins - 1; sh.piv_before = 0; sh.piv_count = 0; }   // (the owner below writes after the barrier)
     __syncthreads();
-    int before = 0;
+    int before = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < kW; ++w) before += (w < wave) ? sh.wtot[w] : 0;
+    for (int w = 0; w < kW; ++w) { before += (w < wave) ? sh.wtot[w] : 0; total += sh.wtot[w]; }
     const int excl = before + incl - loc;
     if (excl < need && need <= excl + loc) {   // exactly one thread owns the pivot bin
         int a = excl, j = 0;
@@ -128,6 +130,7 @@ __device__ __forceinline__ void find_pivot_bin(CompressShared& sh, int need) {
         sh.piv_count = h[j];
     }
     __syncthreads();
+    return total;
 }
 
 // What a prune keeps: key > K, or key == K and id <= I.
@@ -725,9 +728,11 @@ __device__ __forceinline__ void compress_row(
                 STAMP(1);
                 bm = add_stats(e0_t{}, v, true);
             }
+            // smallest value of the sample; the optimistic pass leaves masked vocabulary entries (-inf) out of it,
+            // so that the value range it bins is that of the entries a threshold can fall between
             float bn = __builtin_huge_valf();
 #pragma unroll
-            for (int e = 0; e < E0; ++e) bn = fminf(bn, v[e]);
+            for (int e = 0; e < E0; ++e) bn = fminf(bn, (optimistic && !(v[e] > kNegInf)) ? __builtin_huge_valf() : v[e]);
             // key range of the sample
             const float wmax = wave_max(bm), wmin = -wave_max(-bn);
             if (lane == 0) { sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax)); sh.wkey[kW + wave] = short_key<BF16>(__float_as_uint(wmin)); }
@@ -752,10 +757,21 @@ __device__ __forceinline__ void compress_row(
                     const float scale = 1.0f / width;
 #pragma unroll
                     for (int e = 0; e < E0; ++e)
-                        if (v[e] == v[e]) atomicAdd(&sh.hist[min((int)((vmax - v[e]) * scale), kBins - 1)], 1u);
+                        if (v[e] > kNegInf) atomicAdd(&sh.hist[min((int)((vmax - v[e]) * scale), kBins - 1)], 1u);
                     __syncthreads();
-                    find_pivot_bin(sh, target);
-                    if (scale < __builtin_huge_valf() && sh.piv_count <= max(8, target / 4)) {
+                    const int n_finite = find_pivot_bin(sh, target);
+                    if (n_finite < target) {
+                        // A row that is mostly masked: fewer entries above -inf than the rank aimed at.  Every one
+                        // of them becomes a candidate (there are about n_finite * V / SAMPLE, which fits), unless
+                        // the row very likely holds fewer than k: then the record is filled up with masked entries
+                        // in id order, which only the safe pass lists.
+                        have_tau = true;         // (either way the radix passes below have nothing to find)
+                        if ((int64_t)n_finite * V >= (int64_t)k * (SAMPLE / 2)) {
+                            tau = kNegInf;
+                            admit_all = false;
+                            key_lo = short_key<BF16>(0xFF800000u);
+                        }
+                    } else if (scale < __builtin_huge_valf() && sh.piv_count <= max(8, target / 4)) {
                         const float t = vmax - ((float)(sh.piv_bin + 1) + 0.01f) * width;   // below every element of the bins up to the pivot
                         if (t > kNegInf) {
                             tau = float_below(t);
@@ -781,8 +797,9 @@ __device__ __forceinline__ void compress_row(
                     __syncthreads();
 #pragma unroll
                     for (int e = 0; e < E0; ++e) {
-                        const uint32_t d = short_key<BF16>(__float_as_uint(v[e])) - lo;   // ... keys below lo wrap far above
-                        if (v[e] == v[e] && (pass == 0 || (d >> wbits) == 0)) atomicAdd(&sh.hist[kBins - 1 - (int)(d >> shift)], 1u);
+                        const uint32_t d = short_key<BF16>(__float_as_uint(v[e])) - lo;   // ... keys below lo wrap far above (masked entries below
+                                                                                          //     the optimistic pass's range: left out)
+                        if (v[e] == v[e] && d <= range && (pass == 0 || (d >> wbits) == 0)) atomicAdd(&sh.hist[kBins - 1 - (int)(d >> shift)], 1u);
                     }
                     __syncthreads();
                     find_pivot_bin(sh, need);
@@ -921,7 +938,11 @@ __device__ __forceinline__ void compress_row(
             S = 0.0;
 #pragma unroll
             for (int w = 0; w < kW; ++w) S += sh.red[kW + w];
-            if (tid == kT - 1) lse[row] = (float)((double)M * (double)inv_T + log(S));   // (off the last wave's critical path later on)
+            if (tid == kT - 1) {                 // (off the last wave's critical path later on)
+                float it = inv_T;
+                asm volatile("" : "+s"(it));     // widened here: hoisted to the top of the kernel it would hold two registers throughout
+                lse[row] = (float)((double)M * (double)it + log(S));
+            }
         }
         key_hi = short_key<BF16>(__float_as_uint(M));
         STAMP(6);

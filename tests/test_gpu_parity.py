@@ -76,7 +76,8 @@ def test_compress_sizes_and_tails(gpu, pu, ps, V, k, dtype):
 
 @pytest.mark.parametrize("pattern", ["ties", "all_equal", "ascending", "descending", "neg_inf", "signed_zero",
                                      "two_values", "sawtooth", "trend_down", "trend_up", "head_hot", "head_cold",
-                                     "hot_cluster", "period_of_the_sample"])
+                                     "hot_cluster", "period_of_the_sample", "masked_3pct", "masked_block", "masked_few",
+                                     "masked_half"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
     _announce("compress adversarial", pattern, dtype)
@@ -99,6 +100,15 @@ def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
         z = np.where(rng.random((3, V)) < 0.01, 2.0, -2.0).astype(np.float32)
     elif pattern == "sawtooth":
         z = np.tile((np.arange(V) % 1000).astype(np.float32) * 0.01, (3, 1))
+    elif pattern.startswith("masked"):
+        # vocabulary masks (-inf everywhere but on the allowed ids): more allowed ids than k, fewer than k (the record
+        # is then filled up with masked ids in ascending order), a block of ids, half of the vocabulary
+        z = (rng.standard_normal((3, V)) * 3).astype(np.float32)
+        ids = np.arange(V)
+        allowed = {"masked_3pct": rng.random((3, V)) < 0.03, "masked_few": rng.random((3, V)) < 0.002,
+                   "masked_block": np.tile((ids >= 20000) & (ids < 21500), (3, 1)),
+                   "masked_half": rng.random((3, V)) < 0.5}[pattern]
+        z = np.where(allowed, z, -np.inf).astype(np.float32)
     else:
         # values that depend on the vocabulary id, as logits do (frequent tokens sit at low ids): the threshold
         # comes from a sample spread over the row, and whatever the sample misses the count at the row's end catches
