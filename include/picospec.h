@@ -24,7 +24,9 @@
  *   - Logits are row-major [rows, ld] with ld >= V elements between row starts, dtype
  *     PICOSPEC_F32 or PICOSPEC_BF16; the base pointer must be element-aligned.  Rows need not be
  *     16-byte aligned (aligned rows stream fastest).  Softmax is taken at `temperature` > 0:
- *     P(x) = exp(z_x / T - lse).  NaN or +inf logits give unspecified (but memory-safe) results.
+ *     P(x) = exp(z_x / T - lse).  -inf logits are legal (P = 0: a masked vocabulary entry).  NaN or +inf
+ *     logits, and rows without any finite logit (no distribution exists), give unspecified (but
+ *     memory-safe) results.
  *   - Ragged batch: seq_off[B+1] (int32, device) is the CSR over draft rows, gamma_b =
  *     seq_off[b+1] - seq_off[b] >= 0, N = seq_off[B] is also passed from the host as n_draft.
  *     Target rows are packed with one extra (bonus) row per sequence: position t in 0..gamma_b

@@ -100,7 +100,11 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def _logits_2d(t: torch.Tensor):
-    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+    if t.dim() != 2 or not t.is_cuda:
+        raise PicoSpecError(EINVAL)
+    if t.shape[0] == 0:                       # no rows: the strides of an empty tensor mean nothing
+        return _dtype_code(t), t.shape[1]
+    if t.stride(1) != 1:
         raise PicoSpecError(EINVAL)
     return _dtype_code(t), t.stride(0)
 

@@ -25,6 +25,11 @@ RTOL_LSE = 2e-6
 ACCEPT_MARGIN = 1e-5
 CDF_MARGIN = 1e-6
 TOPP_MARGIN = 1e-6
+# The residual mass is a sum of differences P(x) - qhat(x) of fp32 probabilities in [0, 1] (the record of Eq. 4
+# stores fp32 values; P is formed with one fp32 exponential), each known to about 2^-23 of its own size: where one
+# token carries almost all of the mass on both sides, R is small and its error is absolute, a few 1e-7, not
+# relative to R.  The same holds for the position of u*R on the residual CDF.
+RESID_ATOL = 1e-6
 
 
 def to_device(a: np.ndarray, device) -> torch.Tensor:
@@ -146,10 +151,10 @@ def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: fl
     # u*R lies within CDF_MARGIN (relative to R) of a step of the oracle's CDF
     tok_g = n(g.res.out_tok)
     tok_same = tok_g == o.res.out_tok
-    tok_allowed = o.res.cdf_margin < CDF_MARGIN
+    tok_allowed = o.res.cdf_margin < CDF_MARGIN + RESID_ATOL / np.maximum(o.res.resid_mass, 1e-300)
     assert (tok_same | tok_allowed | ~same).all(), \
         ("out_tok", np.nonzero(same & ~tok_same & ~tok_allowed)[0][:10])
-    st["resid_mass"] = assert_close(n(g.res.resid_mass)[same], o.res.resid_mass[same], RTOL, "resid_mass")
+    st["resid_mass"] = assert_close(n(g.res.resid_mass)[same], o.res.resid_mass[same], RTOL, "resid_mass", atol=RESID_ATOL)
     assert ((n(g.res.flags).astype(np.int64) & 0xFFFFFFFF)[same] == o.res.flags[same]).all(), "residual flags"
     st["mismatch_accept"] = int((~same).sum())           # all of them knife-edge (asserted above)
     st["mismatch_draw"] = int((same & ~tok_same).sum())  # all of them within CDF_MARGIN of a step

@@ -1,0 +1,123 @@
+"""Seeded random sweep of picospec_compress against the oracle: vocabulary sizes around the kernel's internal
+boundaries (the 8192-element sample, sub-tiles of 4096, the 16-byte vectors), record lengths from 1 to 4096,
+both dtypes, temperatures, top-p, rows off the 16-byte boundary, and value patterns that steer the selector
+through its passes (plain, heavy-tailed, trending with the id, masked, tie-heavy)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_19133_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+N_CASES = int(os.environ.get("PICOSPEC_SWEEP_CASES", "480"))     # a multiple of 8; raise it for a longer hunt
+
+
+def _case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    V = int(rng.choice([int(rng.integers(8193, 8300)), int(rng.integers(8300, 12400)), int(rng.integers(12000, 33000)),
+                        int(rng.integers(33000, 70000)), 8192 + 4096 * int(rng.integers(1, 6)) + int(rng.integers(-3, 4)),
+                        int(rng.integers(2, 8193))]))
+    k = int(min(V, 4096, max(1, round(float(np.exp(rng.uniform(0, np.log(4096))))))))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    T = float(rng.choice([0.3, 0.7, 1.0, 1.0, 1.5, 4.0]))
+    top_p = float(rng.choice([0.0, 0.0, 0.5, 0.9, 0.99]))
+    shift = int(rng.choice([0, 0, 0, 1, 2, 3, 5]))
+    pattern = str(rng.choice(["normal", "zipf", "trend", "head", "masked", "ties", "coarse_values"]))
+    rows = 3
+    ld = V + shift
+    ids = np.arange(ld, dtype=np.float64)
+    z = rng.standard_normal((rows, ld)) * float(rng.choice([0.5, 3.0, 8.0]))
+    if pattern == "zipf":
+        z = -1.2 * np.log(np.stack([rng.permutation(ld) for _ in range(rows)]) + 1.0) + 0.5 * rng.standard_normal((rows, ld))
+    elif pattern == "trend":
+        z = z + float(rng.choice([-12.0, -3.0, 3.0, 12.0])) * ids / ld
+    elif pattern == "head":
+        z = z + np.where(ids < float(rng.choice([300, 4096, 8192, 20000])), float(rng.choice([-8.0, 5.0, 9.0])), 0.0)
+    elif pattern == "masked":
+        keep = rng.random((rows, ld)) < float(rng.choice([0.5, 0.05, 0.005]))
+        keep[:, int(rng.integers(shift, ld))] = True        # a row without any finite logit has no distribution
+        z = np.where(keep, z, -np.inf)
+    elif pattern == "ties":
+        z = np.round(z)
+    elif pattern == "coarse_values":
+        z = np.round(z * 4) / 4 + 16.0          # few distinct values, all in one binade
+    return dict(V=V, k=k, dtype=dtype, T=T, top_p=top_p, shift=shift, pattern=pattern), z.astype(np.float32)
+
+
+@pytest.mark.parametrize("block", range(8))
+def test_compress_random_sweep(gpu, block):
+    import parity_util as pu
+    from paper_2603_19133_amd import binding as ps
+    per = N_CASES // 8
+    for seed in range(block * per, (block + 1) * per):
+        c, z = _case(seed)
+        print("[case] sweep", seed, c, flush=True)
+        stored = z if c["dtype"] == "f32" else W.to_bf16_bits(z)
+        dev = pu.to_device(stored, gpu)
+        s = c["shift"]
+        o = oracle.compress(np.ascontiguousarray(stored[:, s:]), c["V"], c["T"], c["k"], c["top_p"])
+        g = ps.compress(dev[:, s:], c["V"], c["T"], c["k"], c["top_p"])
+        torch.cuda.synchronize()
+        pu.compare_compress(g, o, c["top_p"])
+
+
+# ---------------------------------------------------------------- whole rounds
+
+N_ROUNDS = int(os.environ.get("PICOSPEC_SWEEP_ROUNDS", "160"))         # a multiple of 8
+
+
+def _round_case(seed):
+    rng = np.random.default_rng(50_000 + seed)
+    B = int(rng.integers(1, 13))
+    g = rng.integers(0, 7, size=B).astype(np.int32)                    # gamma_b = 0 is legal: only the bonus token
+    off = np.zeros(B + 1, np.int32)
+    off[1:] = np.cumsum(g)
+    N = int(off[-1])
+    V = int(rng.choice([int(rng.integers(2, 300)), int(rng.integers(300, 8193)), int(rng.integers(8193, 9000)),
+                        int(rng.integers(9000, 36000))]))
+    k = int(min(V, 1024, max(1, round(float(np.exp(rng.uniform(0, np.log(1024))))))))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    T = float(rng.choice([0.5, 1.0, 1.0, 2.0]))
+    top_p = float(rng.choice([0.0, 0.0, 0.0, 0.9]))
+    renorm = int(rng.choice([1, 1, 0]))
+    pattern = str(rng.choice(["normal", "zipf", "masked", "peaked"]))
+    tgt = rng.standard_normal((N + B, V)) * float(rng.choice([1.0, 3.0]))
+    if pattern == "zipf":
+        tgt = -1.2 * np.log(np.stack([rng.permutation(V) for _ in range(N + B)]) + 1.0) + 0.5 * tgt
+    elif pattern == "peaked":                                          # one token carries almost all of the mass
+        tgt[np.arange(N + B), rng.integers(0, V, N + B)] += 14.0
+    drows = np.concatenate([np.arange(off[b] + b, off[b] + b + g[b]) for b in range(B)]).astype(np.int64) if N else np.zeros(0, np.int64)
+    draft = tgt[drows] * float(rng.choice([1.0, 0.8])) + rng.standard_normal((N, V)) * float(rng.choice([0.0, 0.3, 1.5]))
+    if pattern == "masked":                                            # the same mask on both sides, one id always allowed
+        keep = rng.random(V) < float(rng.choice([0.5, 0.05]))
+        keep[int(rng.integers(0, V))] = True
+        tgt = np.where(keep, tgt, -np.inf)
+        draft = np.where(keep, draft, -np.inf)
+    conv = (lambda a: a.astype(np.float32)) if dtype == "f32" else (lambda a: W.to_bf16_bits(a.astype(np.float32)))
+    w = W.Workload(f"sweep{seed}", 99, B, 0, 6, V, dtype, T, k, top_p, 1, "sweep")
+    r = W.Round(w, 0, np.arange(B), off, conv(draft).reshape(N, V), conv(tgt), rng.random(N + B, dtype=np.float32),
+                rng.random(N, dtype=np.float32))
+    return dict(B=B, N=N, V=V, k=k, dtype=dtype, T=T, top_p=top_p, renorm=renorm, pattern=pattern), r, renorm
+
+
+@pytest.mark.parametrize("block", range(8))
+def test_round_random_sweep(gpu, block):
+    """Ragged random rounds through the three calls and through picospec_round, against the oracle."""
+    import parity_util as pu
+    from paper_2603_19133_amd import binding as ps
+    per = N_ROUNDS // 8
+    for seed in range(block * per, (block + 1) * per):
+        c, r, renorm = _round_case(seed)
+        print("[case] round sweep", seed, c, flush=True)
+        o = pu.oracle_round(r, renorm=renorm)
+        pu.compare_round(pu.gpu_round(r, o.tok, gpu, renorm=renorm), o, r, max_excluded_frac=0.34)
+        d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+        w = r.workload
+        q, ver, res = ps.round(pu.to_device(r.draft_logits, gpu), pu.to_device(r.tgt_logits, gpu), w.V, w.T, d(r.seq_off),
+                               r.N, d(o.tok), w.k, d(r.uniforms), top_p=w.top_p, renorm=renorm)
+        torch.cuda.synchronize()
+        pu.compare_round(pu.GpuRound(q, ver, res), o, r, max_excluded_frac=0.34)
