@@ -52,14 +52,17 @@ def _downlink(pu, ps, gpu, r, k, renorm, n_accept=None, top_p=0.0):
     if r.N:
         olse = oracle.compress(r.draft_logits, w.V, w.T, 1).lse
         pu.assert_close(pu.n(dlse), olse, pu.RTOL_LSE, "draft lse", atol=2e-6)
-    assert (pu.n(gres.flags).astype(np.uint32) == ores.flags).all()
-    st["resid_mass"] = pu.assert_close(pu.n(gres.resid_mass), ores.resid_mass, pu.RTOL, "resid_mass", atol=1e-30)
+    # a residual mass within the arithmetic's absolute error of zero: whether it counts as empty (flag, fallback
+    # draw from the record) is not decidable in fp32 -- in exact arithmetic such a position is never rejected
+    undecided = ores.resid_mass <= pu.RESID_ATOL
+    assert (pu.n(gres.flags).astype(np.uint32) == ores.flags)[~undecided].all()
+    st["resid_mass"] = pu.assert_close(pu.n(gres.resid_mass), ores.resid_mass, pu.RTOL, "resid_mass", atol=pu.RESID_ATOL)
     same = pu.n(gres.out_tok) == ores.out_tok
-    knife = ores.cdf_margin < pu.CDF_MARGIN
+    knife = (ores.cdf_margin < pu.CDF_MARGIN + pu.RESID_ATOL / np.maximum(ores.resid_mass, 1e-300)) | undecided
     excl = set(st["topp_excluded"])
     for b in np.nonzero(~same)[0]:
         assert knife[b] or b in excl, (b, pu.n(gres.out_tok)[b], ores.out_tok[b], ores.cdf_margin[b])
-    st["mismatch_draw"] = int((~same).sum())
+    st["mismatch_draw"] = int((~same & ~undecided).sum())
     assert st["mismatch_draw"] <= max(1, r.B // 50)
     return st, ores
 

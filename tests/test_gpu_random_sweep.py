@@ -121,3 +121,20 @@ def test_round_random_sweep(gpu, block):
                                r.N, d(o.tok), w.k, d(r.uniforms), top_p=w.top_p, renorm=renorm)
         torch.cuda.synchronize()
         pu.compare_round(pu.GpuRound(q, ver, res), o, r, max_excluded_frac=0.34)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_downlink_and_ranges_random_sweep(gpu, block):
+    """The same random rounds through the paper's own downlink (record of the rejected target row, local
+    resampling at the edge) and through the verification of three consecutive ranges of positions."""
+    import parity_util as pu
+    import test_gpu_downlink as D
+    import test_gpu_verify_range as VR
+    from paper_2603_19133_amd import binding as ps
+    per = N_ROUNDS // 8
+    for seed in range(block * per, (block + 1) * per):
+        c, r, renorm = _round_case(7000 + seed)
+        print("[case] downlink/ranges sweep", seed, c, flush=True)
+        w = r.workload
+        D._downlink(pu, ps, gpu, r, min(w.k, w.V), renorm)
+        VR._ranges_case(pu, ps, gpu, r, w.k, seed)

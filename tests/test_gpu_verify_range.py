@@ -56,11 +56,16 @@ def _compare_range(pu, r, g, o, begin, end):
 def test_ranges_match_the_oracle_and_compose(gpu, pu, ps, name, scale, k):
     _announce("verify_range", name, k)
     w = W.WORKLOADS[name].scaled(**scale)
-    r = W.build_round(w, 0)
+    _ranges_case(pu, ps, gpu, W.build_round(w, 0), k, 3)
+
+
+def _ranges_case(pu, ps, gpu, r, k, seed):
+    """Three consecutive random ranges per sequence: each against the oracle, together against the whole call."""
+    w = r.workload
     q, tok, gq, tgt, seq_off, dtok, uni, d = _setup(pu, ps, gpu, r, k)
     g = np.diff(r.seq_off).astype(np.int32)
     gmax = int(g.max(initial=0))
-    rng = np.random.default_rng(3)
+    rng = np.random.default_rng(seed)
     cut1 = np.array([rng.integers(0, gi + 1) for gi in g], np.int32)
     cut2 = np.array([rng.integers(c, gi + 1) for c, gi in zip(cut1, g)], np.int32)
     whole_o = oracle.verify(r.tgt_logits, w.V, w.T, r.seq_off, tok, q, r.uniforms)
