@@ -138,3 +138,47 @@ def test_downlink_and_ranges_random_sweep(gpu, block):
         w = r.workload
         D._downlink(pu, ps, gpu, r, min(w.k, w.V), renorm)
         VR._ranges_case(pu, ps, gpu, r, w.k, seed)
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_wire_random_sweep(gpu, block):
+    """Random batches of records through the downlink message (bytes against the oracle's, every format, receivers
+    with as many or fewer slots) and random drafts through the uplink message."""
+    import parity_util as pu
+    import test_gpu_wire as Wt
+    from paper_2603_19133_amd import binding as ps
+    per = N_ROUNDS // 4
+    for seed in range(block * per, (block + 1) * per):
+        rng = np.random.default_rng(90_000 + seed)
+        B, k, gmax = int(rng.integers(0, 70)), int(rng.integers(1, 300)), int(rng.integers(0, 17))
+        fmt = int(rng.integers(0, 3))
+        print("[case] wire sweep", seed, dict(B=B, k=k, gmax=gmax, fmt=fmt), flush=True)
+        seq_off, n_accept, token, idx, prob, count = Wt._batch(seed, B, k, gmax=gmax, tiny=bool(seed % 3 == 0))
+        want, n = oracle.pack_downlink(seq_off, n_accept, token, idx, prob, count, fmt)
+        d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+        cap = ps.downlink_bytes_max(B, k, fmt)
+        wire = torch.full((cap + 8,), 0xEE, dtype=torch.uint8, device=gpu)
+        _, nbytes, status = ps.pack_downlink(d(seq_off), d(n_accept), d(token), Wt._rec(ps, gpu, idx, prob, count), fmt, wire=wire)
+        torch.cuda.synchronize()
+        got = wire.cpu().numpy()
+        assert int(nbytes.item()) == n and int(status.item()) == 0
+        assert np.array_equal(got[:n], want) and np.all(got[n:] == 0xEE)
+        for k2 in sorted({k, max(1, k // 3)}):
+            Wt._compare_unpacked(pu, ps.unpack_downlink(d(want), n, B, k2), oracle.unpack_downlink(want, B, k2), k2)
+        # uplink of the same ragged shape
+        N = int(seq_off[-1])
+        tok = rng.integers(0, 152064, N).astype(np.int32)
+        q = np.exp2(rng.uniform(-28, 0, N)).astype(np.float32)
+        wantu, nu = oracle.pack_uplink(seq_off, tok, q, fmt)
+        wu = torch.full((nu + 8,), 0xEE, dtype=torch.uint8, device=gpu)
+        _, nb = ps.pack_uplink(d(seq_off), N, d(tok), d(q), fmt, wire=wu)
+        torch.cuda.synchronize()
+        gotu = wu.cpu().numpy()
+        assert int(nb.item()) == nu and np.array_equal(gotu[:nu], wantu) and np.all(gotu[nu:] == 0xEE)
+        n_max = int(rng.integers(0, N + 3))
+        o = oracle.unpack_uplink(wantu, B, n_max)
+        so, t, qq, st = ps.unpack_uplink(d(wantu), nu, B, n_max)
+        torch.cuda.synchronize()
+        kept = int(o.seq_off[-1])
+        assert int(st.item()) == o.status and np.array_equal(pu.n(so), o.seq_off)
+        assert np.array_equal(pu.n(t)[:kept], o.draft_tok[:kept]) and np.array_equal(pu.n(qq)[:kept].astype(np.float64), o.q_scalar[:kept])
