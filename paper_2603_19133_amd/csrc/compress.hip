@@ -68,7 +68,7 @@ struct __align__(16) CompressShared {
     unsigned coarse[kCoarse];               // rank sort: count, then (fine bins << 16) | first fine bin, per coarse range
     double red[2 * kW];
     int wtot[kW];
-    unsigned wkey[2 * kW];
+    unsigned wkey[3 * kW];                  // per wave: largest key, smallest key, "saw a masked entry" (sample of the optimistic pass)
     int cnt;                                // candidates held
     int n_holes, n_fills;                   // compaction of a prune
     int piv_bin, piv_before, piv_count;     // radix-select broadcast
@@ -254,7 +254,9 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
 
 // Clears what order_top_k counts in; a barrier must lie between this and the call.
 __device__ __forceinline__ void order_prepare(CompressShared& sh, int n) {
-    for (int i = threadIdx.x; i < kCoarse; i += kT) sh.coarse[i] = 0;
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));                  // (the address is formed here, not held in a register from the top of the kernel)
+    for (int i = t; i < kCoarse; i += kT) sh.coarse[i] = 0;
     zero_hist(sh);
     if (threadIdx.x == 0) { sh.maxbin = 0; sh.piv_bin = kBins - 1; sh.piv_before = n; }
 }
@@ -688,6 +690,7 @@ __device__ __forceinline__ void compress_row(
     double S = 0.0;
     uint32_t key_lo = 0, key_hi = 0;
     int n_held = -1;                             // candidates held at the end of the row (-1: read the counter)
+    bool fill = false;                           // fewer entries above -inf than k: masked entries fill the record up
 
     for (int attempt = r_opt > 0 ? 0 : 1; attempt < 2; ++attempt) {
         const bool optimistic = attempt == 0;
@@ -731,18 +734,30 @@ __device__ __forceinline__ void compress_row(
             // smallest value of the sample; the optimistic pass leaves masked vocabulary entries (-inf) out of it,
             // so that the value range it bins is that of the entries a threshold can fall between
             float bn = __builtin_huge_valf();
+            bool saw_masked = false;             // (an element in front of or behind the row counts as one: it only costs a
+                                                 //  constant row that is cut at both ends a pass that fails)
 #pragma unroll
-            for (int e = 0; e < E0; ++e) bn = fminf(bn, (optimistic && !(v[e] > kNegInf)) ? __builtin_huge_valf() : v[e]);
+            for (int e = 0; e < E0; ++e) {
+                const bool above = v[e] > kNegInf;
+                bn = fminf(bn, (optimistic && !above) ? __builtin_huge_valf() : v[e]);
+                saw_masked |= !above;
+            }
             // key range of the sample
             const float wmax = wave_max(bm), wmin = -wave_max(-bn);
-            if (lane == 0) { sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax)); sh.wkey[kW + wave] = short_key<BF16>(__float_as_uint(wmin)); }
+            const unsigned wave_masked = __ballot(saw_masked) != 0ull;
+            if (lane == 0) {
+                sh.wkey[wave] = short_key<BF16>(__float_as_uint(wmax));
+                sh.wkey[kW + wave] = short_key<BF16>(__float_as_uint(wmin));
+                sh.wkey[2 * kW + wave] = wave_masked;
+            }
             const int target = optimistic ? r_opt : k;
             const bool one_pass = optimistic && more && n0 > target;
             if (one_pass) zero_hist(sh);         // (for the histogram below: the barrier of the key range serves it too)
             __syncthreads();
             key_hi = 0; key_lo = 0xFFFFFFFFu;
+            unsigned masked = 0;
 #pragma unroll
-            for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); }
+            for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); masked |= sh.wkey[2 * kW + w]; }
             STAMP(2);
             bool have_tau = false;
             if (one_pass) {
@@ -762,15 +777,12 @@ __device__ __forceinline__ void compress_row(
                     const int n_finite = find_pivot_bin(sh, target);
                     if (n_finite < target) {
                         // A row that is mostly masked: fewer entries above -inf than the rank aimed at.  Every one
-                        // of them becomes a candidate (there are about n_finite * V / SAMPLE, which fits), unless
-                        // the row very likely holds fewer than k: then the record is filled up with masked entries
-                        // in id order, which only the safe pass lists.
-                        have_tau = true;         // (either way the radix passes below have nothing to find)
-                        if ((int64_t)n_finite * V >= (int64_t)k * (SAMPLE / 2)) {
-                            tau = kNegInf;
-                            admit_all = false;
-                            key_lo = short_key<BF16>(0xFF800000u);
-                        }
+                        // of them becomes a candidate (there are about n_finite * V / SAMPLE, which fits); should
+                        // the row hold fewer than k, masked entries fill the record up in id order at the end.
+                        have_tau = true;
+                        tau = kNegInf;
+                        admit_all = false;
+                        key_lo = short_key<BF16>(0xFF800000u);
                     } else if (scale < __builtin_huge_valf() && sh.piv_count <= max(8, target / 4)) {
                         const float t = vmax - ((float)(sh.piv_bin + 1) + 0.01f) * width;   // below every element of the bins up to the pivot
                         if (t > kNegInf) {
@@ -782,6 +794,14 @@ __device__ __forceinline__ void compress_row(
                     }
                     __syncthreads();             // (the histogram and the pivot words are reused below)
                     STAMP(3);
+                } else if (masked && !(vmax > vmin) && vmax < __builtin_huge_valf()) {
+                    // masked entries and at most one value above -inf in the whole sample (a vocabulary mask that
+                    // leaves a handful of ids): every entry above -inf becomes a candidate
+                    have_tau = true;
+                    tau = kNegInf;
+                    admit_all = false;
+                    key_lo = short_key<BF16>(0xFF800000u);
+                    __syncthreads();
                 }
             }
             if (!have_tau && more && n0 > target && key_hi > key_lo) {
@@ -873,8 +893,10 @@ __device__ __forceinline__ void compress_row(
             }
             __syncthreads();
             const int held = sh.cnt >> 2;        // (this pass counts bytes of cand_val)
-            enough = applies && !sh.overflowed && held >= k && held <= kCap;
+            // (a threshold of -inf: every entry above -inf is held, so fewer than k of them are still the whole answer)
+            enough = applies && !sh.overflowed && held <= kCap && (held >= k || (tau == kNegInf && held >= 1));
             n_held = enough ? held : -1;
+            fill = enough && held < k;
             __syncthreads();                     // everyone has read the verdict before the next attempt resets it
         } else {
             // ---- behind the sample, safe: all waves meet after every sub-tile; a full buffer is pruned back to
@@ -969,8 +991,48 @@ __device__ __forceinline__ void compress_row(
 
     // ---- exact cut to k, ordering and emission
     const int n = min(n_held, k);
-    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, k, V, key_lo, key_hi, stamp_out);
+    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, n, V, key_lo, key_hi, stamp_out);
     STAMP(13);
+
+    // A mostly masked row with fewer entries above -inf than k (all of them are held): the record goes on with
+    // masked entries (probability 0), lowest ids first, i.e. with the lowest ids that are not held.  There are
+    // k - n of them among the ids below n + (k - n) <= 2 * kMaxK: a bitmap of the held ids in that range and the
+    // number of free ids in front of each of its words locate the j-th.
+    constexpr int kFillWords = 2 * kMaxK / 32;
+    static_assert(kFillWords <= kT && 2 * kFillWords <= kBins, "the bitmap and its prefix live in the histogram");
+    uint32_t* const held_bits = sh.hist;
+    uint32_t* const free_before = sh.hist + kFillWords;
+    if (fill) {
+        int t = tid;
+        asm volatile("" : "+v"(t));              // (addresses formed here, in this rare branch, not held from the top of the kernel)
+        if (t < kFillWords) held_bits[t] = 0u;
+        __syncthreads();
+        for (int i = t; i < n; i += kT) {
+            const uint32_t id = kIdMask - ((uint32_t)sorted[i] & kIdMask);
+            if (id < 2u * kMaxK) atomicOr(&held_bits[id >> 5], 1u << (id & 31u));
+        }
+        __syncthreads();
+        const int z = t < kFillWords ? 32 - __popc(held_bits[t]) : 0;
+        const int incl = wave_scan_incl(z);
+        if (lane == kWave - 1) sh.wtot[wave] = incl;
+        __syncthreads();
+        int before = 0;
+#pragma unroll
+        for (int w = 0; w < kW; ++w) before += (w < wave) ? sh.wtot[w] : 0;
+        if (t < kFillWords) free_before[t] = (uint32_t)(before + incl - z);
+        __syncthreads();
+    }
+    auto filler = [&](int j) {                   // the j-th lowest id that is not held
+        int lo = 0, hi = kFillWords - 1;         // the last word with at most j free ids in front of it
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if ((int)free_before[mid] <= j) lo = mid; else hi = mid - 1;
+        }
+        uint32_t free = ~held_bits[lo];
+        for (int r = j - (int)free_before[lo]; r > 0; --r) free &= free - 1u;
+        return lo * 32 + __ffs((int)free) - 1;
+    };
+    const int n_out = fill ? k : n;              // slots that hold an entry
 
     // the dropped loads have landed (they were issued a whole ordering ago); waiting here, in front of the
     // record's stores, keeps the wave from waiting for those at its end
@@ -984,6 +1046,7 @@ __device__ __forceinline__ void compress_row(
     int32_t* idx_row = idx + row * (int64_t)k;
     float* prob_row = prob + row * (int64_t)k;
     auto emit_value = [&](int slot, int& id, float& pr) {
+        if (slot >= n) { id = filler(slot - n); pr = 0.f; return; }
         const uint64_t cv = sorted[slot];
         id = (int)(kIdMask - ((uint32_t)cv & kIdMask));
         const float x = __uint_as_float(bits_of_short_key<BF16>((uint32_t)(cv >> kIdBits)));
@@ -1004,7 +1067,7 @@ __device__ __forceinline__ void compress_row(
                 f32x4_t prs = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (s0 + e < n) {
+                    if (s0 + e < n_out) {
                         int id; float pr;
                         emit_value(s0 + e, id, pr);
                         ids[e] = id; prs[e] = pr;
@@ -1021,7 +1084,7 @@ __device__ __forceinline__ void compress_row(
             if (slot < k) {
                 int id = -1;
                 float pr = 0.f;
-                if (slot < n) { emit_value(slot, id, pr); my_mass += (double)pr; ++my_count; }
+                if (slot < n_out) { emit_value(slot, id, pr); my_mass += (double)pr; ++my_count; }
                 __builtin_nontemporal_store(id, &idx_row[slot]);
                 __builtin_nontemporal_store(pr, &prob_row[slot]);
             }
@@ -1031,7 +1094,7 @@ __device__ __forceinline__ void compress_row(
             const int slot = j0 + tid;
             int id = -1;
             float pr = 0.f;
-            if (slot < n) emit_value(slot, id, pr);
+            if (slot < n_out) emit_value(slot, id, pr);
             const double mine = (double)pr;
             const double incl = wave_scan_incl(mine);
             if (lane == kWave - 1) sh.red[wave] = incl;
@@ -1040,7 +1103,7 @@ __device__ __forceinline__ void compress_row(
 #pragma unroll
             for (int w = 0; w < kW; ++w) { const double t = sh.red[w]; if (w < wave) before += t; tot += t; }
             __syncthreads();
-            const bool keep = slot < n && (before + incl - mine) < (double)top_p;
+            const bool keep = slot < n_out && (before + incl - mine) < (double)top_p;
             carry += tot;
             if (slot < k) {
                 idx_row[slot] = keep ? id : -1;
