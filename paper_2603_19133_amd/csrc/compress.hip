@@ -1032,7 +1032,6 @@ __device__ __forceinline__ void compress_row(
         for (int r = j - (int)free_before[lo]; r > 0; --r) free &= free - 1u;
         return lo * 32 + __ffs((int)free) - 1;
     };
-    const int n_out = fill ? k : n;              // slots that hold an entry
 
     // the dropped loads have landed (they were issued a whole ordering ago); waiting here, in front of the
     // record's stores, keeps the wave from waiting for those at its end
@@ -1046,14 +1045,24 @@ __device__ __forceinline__ void compress_row(
     int32_t* idx_row = idx + row * (int64_t)k;
     float* prob_row = prob + row * (int64_t)k;
     auto emit_value = [&](int slot, int& id, float& pr) {
-        if (slot >= n) { id = filler(slot - n); pr = 0.f; return; }
         const uint64_t cv = sorted[slot];
         id = (int)(kIdMask - ((uint32_t)cv & kIdMask));
         const float x = __uint_as_float(bits_of_short_key<BF16>((uint32_t)(cv >> kIdBits)));
         pr = (float)(exp_emit(x, M, cd) * invS);
     };
     const bool rows_aligned = (k & 3) == 0 && ((((uintptr_t)idx_row) | ((uintptr_t)prob_row)) & 15u) == 0;
-    if (!use_top_p && rows_aligned) {
+    if (fill && !use_top_p) {
+        // (rare: a plain loop; with top-p the entries above -inf carry all of the mass, so the prefix that reaches
+        //  top_p ends among them and the loop below needs no fillers)
+        for (int slot = tid; slot < k; slot += kT) {
+            int id;
+            float pr = 0.f;
+            if (slot < n) { emit_value(slot, id, pr); my_mass += (double)pr; } else id = filler(slot - n);
+            ++my_count;
+            idx_row[slot] = id;
+            prob_row[slot] = pr;
+        }
+    } else if (!use_top_p && rows_aligned) {
         // every slot is independent.  A thread takes four consecutive slots and writes them with one
         // 16-byte store per array; the record is not read again by this kernel: non-temporal stores.
         static_assert(kSortPer % 4 == 0, "four slots per thread and step");
@@ -1067,7 +1076,7 @@ __device__ __forceinline__ void compress_row(
                 f32x4_t prs = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (s0 + e < n_out) {
+                    if (s0 + e < n) {
                         int id; float pr;
                         emit_value(s0 + e, id, pr);
                         ids[e] = id; prs[e] = pr;
@@ -1084,7 +1093,7 @@ __device__ __forceinline__ void compress_row(
             if (slot < k) {
                 int id = -1;
                 float pr = 0.f;
-                if (slot < n_out) { emit_value(slot, id, pr); my_mass += (double)pr; ++my_count; }
+                if (slot < n) { emit_value(slot, id, pr); my_mass += (double)pr; ++my_count; }
                 __builtin_nontemporal_store(id, &idx_row[slot]);
                 __builtin_nontemporal_store(pr, &prob_row[slot]);
             }
@@ -1094,7 +1103,7 @@ __device__ __forceinline__ void compress_row(
             const int slot = j0 + tid;
             int id = -1;
             float pr = 0.f;
-            if (slot < n_out) emit_value(slot, id, pr);
+            if (slot < n) emit_value(slot, id, pr);
             const double mine = (double)pr;
             const double incl = wave_scan_incl(mine);
             if (lane == kWave - 1) sh.red[wave] = incl;
@@ -1103,7 +1112,7 @@ __device__ __forceinline__ void compress_row(
 #pragma unroll
             for (int w = 0; w < kW; ++w) { const double t = sh.red[w]; if (w < wave) before += t; tot += t; }
             __syncthreads();
-            const bool keep = slot < n_out && (before + incl - mine) < (double)top_p;
+            const bool keep = slot < n && (before + incl - mine) < (double)top_p;
             carry += tot;
             if (slot < k) {
                 idx_row[slot] = keep ? id : -1;
