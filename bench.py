@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM traffic of one compress launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
 # the same counters' reading for a plain copy kernel of known size; see profiles/.  Bytes per launch.
-MEASURED_TRAFFIC = {"cfg4": 2.670e9, "cfg5": 1.382e9, "cfg3": 1.364e8}   # profiles/*.md
+MEASURED_TRAFFIC = {"cfg4": 2.672e9, "cfg5": 1.387e9, "cfg3": 1.364e8}   # profiles/*.md
 
 
 def algorithmic_bytes(w, N, B):
