@@ -448,7 +448,8 @@ __device__ __forceinline__ void compress_row(
 #endif
     constexpr int RING = PICOSPEC_COMPRESS_RING * (2 / SV);  // sub-tile buffers: one in use, the others in flight
     static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: what is indexed by it is addressed from a scalar
     // Row read: the same one, or (downlink record, Section 3.3) the target row of sequence `row` at its
     // first rejected or bonus position, seq_off[b] + b + n_accept[b] (n_accept clamped to 0..gamma_b).
     int64_t in_row = row;
@@ -900,7 +901,8 @@ __device__ __forceinline__ void compress_row(
             __syncthreads();                     // everyone has read the verdict before the next attempt resets it
         } else {
             // ---- behind the sample, safe: all waves meet after every sub-tile; a full buffer is pruned back to
-            //      the exact top k of everything seen, after which admission is strict.  (Rare path: no prefetch.)
+            //      the exact top k of everything seen, after which admission is strict for the sub-tiles that follow.
+            //      (Rare path: no prefetch.)
             int epoch = 0;
             __syncthreads();
             for (int sub = T0; sub < n_sub; ++sub) {
@@ -912,9 +914,15 @@ __device__ __forceinline__ void compress_row(
                 add_stats(es_t{}, v, edge);
                 const int x0 = sub * SUB - rv.o + tid * N;
                 bool pending = true;
+                // Admission is strict (v > tau) against what earlier sub-tiles left in the buffer: an equal value that
+                // comes later has the higher id and loses the tie.  Inside a sub-tile the waves append in any order, so
+                // after a prune in mid sub-tile the waves still waiting may hold values equal to the k-th with LOWER ids
+                // than entries the prune kept: they are admitted from the k-th value on (the next prune sorts it out).
+                float tau_sub = tau;
+                bool all_sub = admit_all;
                 for (;;) {
                     if (pending) {
-                        const int failed_at = append(sv_t{}, v, tau, admit_all, x0);
+                        const int failed_at = append(sv_t{}, v, tau_sub, all_sub, x0);
                         pending = failed_at >= 0;
                         if (pending && lane == 0) {
                             atomicMin(&sh.epoch_valid[epoch], failed_at);
@@ -937,6 +945,8 @@ __device__ __forceinline__ void compress_row(
                     tau = prune_to_k<BF16>(sh, n_held, k, key_lo, key_hi);
                     admit_all = false;
                     key_lo = short_key<BF16>(__float_as_uint(tau));
+                    tau_sub = float_below(tau);
+                    all_sub = tau == kNegInf;    // (the k-th is a masked entry: the waiting waves' masked entries count too)
                 }
             }
         }

@@ -121,6 +121,18 @@ def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
     _compress_case(pu, ps, gpu, z, V, 1.3, k, dtype=dtype)
 
 
+@pytest.mark.parametrize("V,k,scale", [(10108, 1400, 0.5), (10108, 1700, 0.5), (12300, 2000, 0.5), (16500, 3000, 0.5)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_ties_at_the_cut_when_the_buffer_fills_in_mid_sub_tile(gpu, pu, ps, V, k, scale, dtype):
+    """Rows of a few distinct values whose k-th largest is shared by hundreds of entries, of a length at which
+    the candidate buffer fills while the last sub-tiles are appended: the waves of a sub-tile append in any order,
+    so the ties that wait through a prune must still be able to displace kept ones with higher ids."""
+    _announce("compress ties at the cut", V, k, scale, dtype)
+    rng = np.random.default_rng(V + k)
+    z = np.round(rng.standard_normal((16, V)) * scale).astype(np.float32)
+    _compress_case(pu, ps, gpu, z, V, 1.5, k, dtype=dtype)
+
+
 @pytest.mark.parametrize("shift", [1, 2, 3, 5])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_compress_unaligned_rows(gpu, pu, ps, shift, dtype):
