@@ -14,6 +14,7 @@ from paper_2603_19133_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 N_CASES = int(os.environ.get("PICOSPEC_SWEEP_CASES", "480"))     # a multiple of 8; raise it for a longer hunt
+SEED0 = int(os.environ.get("PICOSPEC_SWEEP_SEED", "0"))          # first seed: move it to hunt on fresh cases
 
 
 def _case(seed):
@@ -26,7 +27,7 @@ def _case(seed):
     T = float(rng.choice([0.3, 0.7, 1.0, 1.0, 1.5, 4.0]))
     top_p = float(rng.choice([0.0, 0.0, 0.5, 0.9, 0.99]))
     shift = int(rng.choice([0, 0, 0, 1, 2, 3, 5]))
-    pattern = str(rng.choice(["normal", "zipf", "trend", "head", "masked", "ties", "coarse_values"]))
+    pattern = str(rng.choice(["normal", "zipf", "trend", "head", "masked", "ties", "coarse_values", "few_values", "ramp"]))
     rows = 3
     ld = V + shift
     ids = np.arange(ld, dtype=np.float64)
@@ -45,6 +46,14 @@ def _case(seed):
         z = np.round(z)
     elif pattern == "coarse_values":
         z = np.round(z * 4) / 4 + 16.0          # few distinct values, all in one binade
+    elif pattern == "few_values":               # three to seven distinct values: the k-th largest is shared by very many
+        z = np.round(rng.standard_normal((rows, ld)) * float(rng.choice([0.3, 0.5, 0.7, 1.0])))
+        if rng.random() < 0.3:
+            z = np.where(rng.random((rows, ld)) < 0.02, -np.inf, z)
+    elif pattern == "ramp":                     # values that rise or fall along the row in steps, with ties inside a step
+        steps = int(rng.choice([3, 17, 200, 5000]))
+        z = np.floor(ids * steps / ld)[None, :] * float(rng.choice([-1.0, 1.0])) + np.zeros((rows, 1))
+        top_p = 0.0                             # (identical rows: one cumulative sum on the threshold would exclude them all)
     return dict(V=V, k=k, dtype=dtype, T=T, top_p=top_p, shift=shift, pattern=pattern), z.astype(np.float32)
 
 
@@ -53,7 +62,7 @@ def test_compress_random_sweep(gpu, block):
     import parity_util as pu
     from paper_2603_19133_amd import binding as ps
     per = N_CASES // 8
-    for seed in range(block * per, (block + 1) * per):
+    for seed in range(SEED0 + block * per, SEED0 + (block + 1) * per):
         c, z = _case(seed)
         print("[case] sweep", seed, c, flush=True)
         stored = z if c["dtype"] == "f32" else W.to_bf16_bits(z)
@@ -113,7 +122,7 @@ def test_round_random_sweep(gpu, block):
     import parity_util as pu
     from paper_2603_19133_amd import binding as ps
     per = N_ROUNDS // 8
-    for seed in range(block * per, (block + 1) * per):
+    for seed in range(SEED0 + block * per, SEED0 + (block + 1) * per):
         c, r, renorm = _round_case(seed)
         print("[case] round sweep", seed, c, flush=True)
         o = pu.oracle_round(r, renorm=renorm)
@@ -135,7 +144,7 @@ def test_downlink_and_ranges_random_sweep(gpu, block):
     import test_gpu_verify_range as VR
     from paper_2603_19133_amd import binding as ps
     per = N_ROUNDS // 8
-    for seed in range(block * per, (block + 1) * per):
+    for seed in range(SEED0 + block * per, SEED0 + (block + 1) * per):
         c, r, renorm = _round_case(7000 + seed)
         print("[case] downlink/ranges sweep", seed, c, flush=True)
         w = r.workload
@@ -151,7 +160,7 @@ def test_wire_random_sweep(gpu, block):
     import test_gpu_wire as Wt
     from paper_2603_19133_amd import binding as ps
     per = N_ROUNDS // 4
-    for seed in range(block * per, (block + 1) * per):
+    for seed in range(SEED0 + block * per, SEED0 + (block + 1) * per):
         rng = np.random.default_rng(90_000 + seed)
         B, k, gmax = int(rng.integers(0, 70)), int(rng.integers(1, 300)), int(rng.integers(0, 17))
         fmt = int(rng.integers(0, 3))
