@@ -21,7 +21,7 @@ def _case(seed):
     rng = np.random.default_rng(1000 + seed)
     V = int(rng.choice([int(rng.integers(8193, 8300)), int(rng.integers(8300, 12400)), int(rng.integers(12000, 33000)),
                         int(rng.integers(33000, 70000)), 8192 + 4096 * int(rng.integers(1, 6)) + int(rng.integers(-3, 4)),
-                        int(rng.integers(2, 8193))]))
+                        int(rng.integers(2, 8193)), int(rng.integers(100_000, 270_000))]))
     k = int(min(V, 4096, max(1, round(float(np.exp(rng.uniform(0, np.log(4096))))))))
     dtype = str(rng.choice(["f32", "bf16"]))
     T = float(rng.choice([0.3, 0.7, 1.0, 1.0, 1.5, 4.0]))
