@@ -381,7 +381,11 @@ def test_sample_draft_record_shapes(gpu, pu, ps, k):
     beyond the longest record the compressor writes), with ragged counts, empty rows and zero weights at the
     end; both sides get the same fp32 record."""
     _announce("sample_draft shapes", k)
-    rng = np.random.default_rng(k)
+    _sample_draft_case(gpu, pu, ps, k, k)
+
+
+def _sample_draft_case(gpu, pu, ps, k, seed):
+    rng = np.random.default_rng(seed)
     rows = 97
     count = rng.integers(0, k + 1, rows).astype(np.int32)
     count[:5] = [k, 0, 1, min(k, 3), max(k - 1, 0)]

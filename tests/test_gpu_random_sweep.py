@@ -194,3 +194,15 @@ def test_wire_random_sweep(gpu, block):
         kept = int(o.seq_off[-1])
         assert int(st.item()) == o.status and np.array_equal(pu.n(so), o.seq_off)
         assert np.array_equal(pu.n(t)[:kept], o.draft_tok[:kept]) and np.array_equal(pu.n(qq)[:kept].astype(np.float64), o.q_scalar[:kept])
+
+
+def test_sample_draft_random_sweep(gpu):
+    """The drafter's draw over records of random lengths (1 to 5000 slots, rows on and off 16-byte boundaries)."""
+    import parity_util as pu
+    import test_gpu_parity as P
+    from paper_2603_19133_amd import binding as ps
+    for seed in range(SEED0, SEED0 + N_ROUNDS // 2):
+        rng = np.random.default_rng(120_000 + seed)
+        k = int(min(5000, max(1, round(float(np.exp(rng.uniform(0, np.log(5000))))))))
+        print("[case] sample_draft sweep", seed, k, flush=True)
+        P._sample_draft_case(gpu, pu, ps, k, 120_000 + seed)
