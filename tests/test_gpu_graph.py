@@ -78,3 +78,32 @@ def test_graph_replays_match_eager(gpu, ps, pu, name, scale, one_call):
             assert torch.equal(v, eager[i][k]), (i, k)
         scratch = torch.randn(1 << 16, device=gpu).sum().item()           # eager work between the replays
         assert np.isfinite(scratch)
+
+
+def test_calls_on_two_streams_do_not_disturb_each_other(gpu, ps, pu):
+    """The library keeps no mutable state between calls: two rounds enqueued on two streams at the same time give
+    what each gives alone."""
+    print("[case] two streams", flush=True)
+    ws = [W.WORKLOADS["cfg3"].scaled(B=24), W.WORKLOADS["cfg4"].scaled(B=10)]
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+    jobs = []
+    for w in ws:
+        r = W.build_round(w, 0)
+        draft, tgt = pu.to_device(r.draft_logits, gpu), pu.to_device(r.tgt_logits, gpu)
+        q = ps.compress(draft, w.V, w.T, w.k, w.top_p)
+        tok, _ = ps.sample_draft(q, d(r.draft_uniforms))
+        args = (draft, tgt, w.V, w.T, d(r.seq_off), r.N, tok, w.k, d(r.uniforms))
+        alone = ps.round(*args, top_p=w.top_p)
+        torch.cuda.synchronize()
+        jobs.append((args, w, {k: v.clone() for k, v in _fields(*alone).items()}))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(5):
+        outs = []
+        for (args, w, _), s in zip(jobs, streams):
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                outs.append(ps.round(*args, top_p=w.top_p))
+        torch.cuda.synchronize()
+        for (args, w, want), got in zip(jobs, outs):
+            for k, v in _fields(*got).items():
+                assert torch.equal(v, want[k]), (rep, w.name, k)

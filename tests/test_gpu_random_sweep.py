@@ -91,6 +91,8 @@ def _round_case(seed):
                         int(rng.integers(9000, 36000))]))
     if big:
         V = min(V, int(rng.integers(50, 3000)))
+    elif B <= 3 and rng.random() < 0.5:                                # a few sequences over a long vocabulary: many tiles
+        V = int(rng.integers(100_000, 300_000))
     k = int(min(V, 1024, max(1, round(float(np.exp(rng.uniform(0, np.log(1024))))))))
     dtype = str(rng.choice(["f32", "bf16"]))
     T = float(rng.choice([0.5, 1.0, 1.0, 2.0]))
