@@ -154,6 +154,36 @@ def test_compress_unaligned_rows(gpu, pu, ps, shift, dtype):
     pu.compare_compress(g2, o2)
 
 
+@pytest.mark.parametrize("pattern", ["trend", "masked_above_k", "masked_below_k", "few_values", "mixed"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_every_pass_with_the_chip_full(gpu, pu, ps, pattern, dtype):
+    """1100 rows (two generations of workgroups, look-ahead loads live) of the kinds that steer the selector through
+    its other passes: values that trend with the id, masks that leave more or fewer ids than k, rows of a few
+    distinct values whose buffer fills, and all of them mixed row by row."""
+    _announce("compress chip full", pattern, dtype)
+    rows, V, k = 1100, 12300, 600
+    rng = np.random.default_rng(len(pattern))
+    ids = np.arange(V, dtype=np.float64)
+    base = rng.standard_normal((rows, V)) * 3
+
+    def make(p, z):
+        if p == "trend":
+            return z + 9.0 * ids / V * rng.choice([-1.0, 1.0], (z.shape[0], 1))
+        if p == "masked_above_k":
+            return np.where(rng.random(z.shape) < 0.15, z, -np.inf)
+        if p == "masked_below_k":
+            return np.where(rng.random(z.shape) < 0.01, z, -np.inf)
+        return np.round(z / 6.0)                                   # few_values: five to seven levels
+
+    if pattern == "mixed":
+        kinds = ["trend", "masked_above_k", "masked_below_k", "few_values"]
+        z = np.concatenate([make(kinds[i % 4], base[i:i + 1]) for i in range(rows)])
+    else:
+        z = make(pattern, base)
+    z[:, 0] = np.where(np.isfinite(z[:, 0]), z[:, 0], 0.0)          # (no row without a finite entry)
+    _compress_case(pu, ps, gpu, z.astype(np.float32), V, 1.0, k, dtype=dtype)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_compress_more_rows_than_resident_workgroups(gpu, pu, ps, dtype):
     """More rows than the chip holds at a time (the look-ahead loads of the next generation of rows are
