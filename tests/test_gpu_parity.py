@@ -160,8 +160,17 @@ def test_compress_every_pass_with_the_chip_full(gpu, pu, ps, pattern, dtype):
     """1100 rows (two generations of workgroups, look-ahead loads live) of the kinds that steer the selector through
     its other passes: values that trend with the id, masks that leave more or fewer ids than k, rows of a few
     distinct values whose buffer fills, and all of them mixed row by row."""
-    _announce("compress chip full", pattern, dtype)
-    rows, V, k = 1100, 12300, 600
+    _chip_full_case(gpu, pu, ps, pattern, dtype, 1100, 12300, 600)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_every_pass_at_full_size(gpu, pu, ps, dtype):
+    """The same mixture at the largest configuration's row length and record length (600 rows)."""
+    _chip_full_case(gpu, pu, ps, "mixed", dtype, 600, 151936, 4096)
+
+
+def _chip_full_case(gpu, pu, ps, pattern, dtype, rows, V, k):
+    _announce("compress chip full", pattern, dtype, rows, V, k)
     rng = np.random.default_rng(len(pattern))
     ids = np.arange(V, dtype=np.float64)
     base = rng.standard_normal((rows, V)) * 3
