@@ -153,13 +153,15 @@ def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: fl
     tok_same = tok_g == o.res.out_tok
     # (a residual mass within RESID_ATOL of zero: whether it counts as empty is not decidable in fp32)
     undecided = o.res.resid_mass <= RESID_ATOL       # (the oracle reports 0 for an empty residual)
-    tok_allowed = (o.res.cdf_margin < CDF_MARGIN + RESID_ATOL / np.maximum(o.res.resid_mass, 1e-300)) | undecided
+    tok_allowed = (o.res.cdf_margin < CDF_MARGIN + RESID_ATOL / np.maximum(o.res.resid_mass, 1e-300)) | undecided | tainted
     assert (tok_same | tok_allowed | ~same).all(), \
         ("out_tok", np.nonzero(same & ~tok_same & ~tok_allowed)[0][:10])
-    st["resid_mass"] = assert_close(n(g.res.resid_mass)[same], o.res.resid_mass[same], RTOL, "resid_mass", atol=RESID_ATOL)
-    assert ((n(g.res.flags).astype(np.int64) & 0xFFFFFFFF)[same & ~undecided] == o.res.flags[same & ~undecided]).all(), "residual flags"
+    # (a sequence with a record on the top-p knife edge may draw against a record one entry longer or shorter)
+    clean = same & ~tainted
+    st["resid_mass"] = assert_close(n(g.res.resid_mass)[clean], o.res.resid_mass[clean], RTOL, "resid_mass", atol=RESID_ATOL)
+    assert ((n(g.res.flags).astype(np.int64) & 0xFFFFFFFF)[clean & ~undecided] == o.res.flags[clean & ~undecided]).all(), "residual flags"
     st["mismatch_accept"] = int((~same).sum())           # all of them knife-edge (asserted above)
-    st["mismatch_draw"] = int((same & ~tok_same & ~undecided).sum())  # all of them within CDF_MARGIN of a step
+    st["mismatch_draw"] = int((same & ~tok_same & ~undecided & ~tainted).sum())  # all of them within CDF_MARGIN of a step
     assert st["mismatch_accept"] <= max(1, int(max_excluded_frac * B)), st
     assert st["mismatch_draw"] <= max(1, int(max_excluded_frac * B)), st
     st["accept_rate"] = float(o.ver.n_accept.sum() / max(1, r.N))
