@@ -21,8 +21,12 @@
 //     the sample is the row's first 8192 elements, which are kept as candidates, and r = k, so the
 //     threshold is at or below the k-th largest of the sample.  The waves meet after
 //     every sub-tile; when the buffer is full it is pruned to the exact top k of everything seen,
-//     and from then on an element must be strictly larger than the k-th (rows are streamed in
-//     ascending id, so equal logits that come later lose the tie).
+//     and from then on an element of a later sub-tile must be strictly larger than the k-th (rows
+//     are streamed in ascending id, so equal logits that come later lose the tie; the waves of the
+//     sub-tile in which the prune happened append in any order and are admitted from the k-th on).
+//   * Vocabulary masks: -inf entries stay out of the optimistic pass's value range; when the sample
+//     shows fewer entries above -inf than the rank aimed at, every such entry of the row becomes a
+//     candidate, and a record they do not fill goes on with masked ids in ascending order.
 //   * The candidates are cut to exactly k and ordered in one step by a histogram rank sort on the
 //     composite
 //         (key << 20) | (2^20 - 1 - id)
