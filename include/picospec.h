@@ -73,7 +73,8 @@ enum {
     PICOSPEC_FLAG_TOKEN_NOT_IN_SUPPORT = 1u, /* a drafted token was absent from its compressed row: treated as q = 0 (accepted) */
     PICOSPEC_FLAG_NONFINITE = 2u,            /* a target row's log-sum-exp is not finite */
     PICOSPEC_FLAG_RESIDUAL_EMPTY = 4u,       /* residual mass <= 0: the token was drawn from P itself */
-    PICOSPEC_FLAG_BAD_INPUT = 8u             /* token id outside [0,V), negative gamma_b, n_accept outside [0,gamma_b] */
+    PICOSPEC_FLAG_BAD_INPUT = 8u             /* token id outside [0,V) (p = 0: rejected, with or without q_scalar), negative gamma_b,
+                                                n_accept outside [0,gamma_b] (clamped) */
 };
 
 enum { PICOSPEC_CALL_COMPRESS = 0, PICOSPEC_CALL_SAMPLE_DRAFT = 1, PICOSPEC_CALL_VERIFY = 2, PICOSPEC_CALL_SAMPLE_RESIDUAL = 3,
@@ -323,6 +324,27 @@ int picospec_pack_uplink(int32_t B, int32_t n_draft, const int32_t* seq_off, con
  */
 int picospec_unpack_uplink(const void* wire, int64_t wire_bytes, int32_t B, int32_t n_max,
                            int32_t* seq_off, int32_t* draft_tok, float* q_scalar, uint32_t* status, void* stream);
+
+/*
+ * host: memory-safety check of the streaming row loads.  For a row of V elements whose first byte lies
+ * misalign_bytes (0..15, a multiple of the element size) above a 16-byte boundary, the end (exclusive), in bytes
+ * from the row's first byte, of the highest byte that the row loads of picospec_compress (which_call =
+ * PICOSPEC_CALL_COMPRESS; also picospec_compress_rejected and picospec_round) or of picospec_sample_residual
+ * (PICOSPEC_CALL_SAMPLE_RESIDUAL) can address, look-ahead loads behind the row included.  The library guarantees
+ * that this lies inside the aligned 16-byte block that holds the row's last byte (a block that holds a valid byte
+ * cannot leave that byte's page); the function evaluates the kernels' own addressing rule over every lane, so a test
+ * can hold the library to it without a GPU.  The rule rests on one property of the device's buffer loads, which
+ * picospec_check_device() tests.  -1 for arguments out of range.
+ */
+int64_t picospec_max_load_byte(int which_call, int dtype, int32_t V, int32_t misalign_bytes);
+
+/*
+ * Device self-check (enqueues two small kernels): does a raw buffer load of the current device range-check the
+ * way the row kernels assume (scalar offset + per-lane offset + 16 <= descriptor size, else the lane reads zero and
+ * touches no memory)?  *status (device uint32) = 0 if so, else one bit per failed probe.  workspace: >= 64 KiB of
+ * device memory on a 16-byte boundary, overwritten; every address the probes form lies inside it.
+ */
+int picospec_check_device(void* workspace, size_t workspace_bytes, uint32_t* status, void* stream);
 
 /* host: bytes of device workspace the given call needs for (dtype, rows, V, k); 0 if none. */
 size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k);

@@ -26,7 +26,7 @@ WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 EXPORTS = ("picospec_round", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
-           "picospec_downlink_bytes_max", "picospec_uplink_bytes",
+           "picospec_downlink_bytes_max", "picospec_uplink_bytes", "picospec_max_load_byte", "picospec_check_device",
            "picospec_workspace_bytes", "picospec_limit", "picospec_strerror", "picospec_version")
 
 if not os.path.exists(LIB_PATH):
@@ -59,6 +59,10 @@ lib.picospec_downlink_bytes_max.argtypes = [_i32, _i32, C.c_int]
 lib.picospec_downlink_bytes_max.restype = _i64
 lib.picospec_uplink_bytes.argtypes = [_i32, _i32, C.c_int]
 lib.picospec_uplink_bytes.restype = _i64
+lib.picospec_max_load_byte.argtypes = [C.c_int, C.c_int, _i32, _i32]
+lib.picospec_max_load_byte.restype = _i64
+lib.picospec_check_device.argtypes = [_p, _sz, _p, _p]
+lib.picospec_check_device.restype = C.c_int
 lib.picospec_workspace_bytes.argtypes = [C.c_int, C.c_int, _i32, _i32, _i32]
 lib.picospec_workspace_bytes.restype = _sz
 lib.picospec_limit.argtypes = [C.c_int]
@@ -355,6 +359,18 @@ def unpack_uplink(wire: torch.Tensor, wire_bytes: int, B: int, n_max: int):
     _check(lib.picospec_unpack_uplink(_ptr(wire), wire_bytes, B, n_max, _ptr(seq_off), _ptr(tok), _ptr(q),
                                       _ptr(status), _stream()))
     return seq_off, tok, q, status
+
+
+def check_device(device) -> int:
+    """picospec_check_device -> status word (0: the device's buffer loads range-check as the row kernels assume)."""
+    ws = torch.empty(64 * 1024, dtype=torch.uint8, device=device)
+    status = torch.full((1,), -1, dtype=torch.int32, device=device)
+    _check(lib.picospec_check_device(_ptr(ws), ws.numel(), _ptr(status), _stream()))
+    return int(status.item()) & 0xFFFFFFFF
+
+
+def max_load_byte(which: int, dtype: int, V: int, misalign_bytes: int) -> int:
+    return int(lib.picospec_max_load_byte(which, dtype, V, misalign_bytes))
 
 
 def workspace_bytes(which: int, dtype: int, rows: int, V: int, k: int) -> int:

@@ -2,9 +2,11 @@
 // onto the gfx950 kernels.  Nothing is launched unless every host-checkable argument is valid.
 #include "../../include/picospec.h"
 
+#include <algorithm>
 #include <cmath>
 
 #include "kernels.hpp"
+#include "rowspan.hpp"
 
 using namespace picospec;
 
@@ -31,6 +33,36 @@ int check_workspace(int which, int dtype, int64_t rows, int32_t V, int32_t k, co
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? PICOSPEC_OK : PICOSPEC_EHIP; }
+
+}  // namespace
+
+namespace {
+
+template <bool BF16>
+int64_t max_load_end(int which, int V, int o)
+{
+    const int N = BF16 ? 8 : 4;
+    const int L = o + V, nq = (L + N - 1) / N;
+    const int64_t size = (int64_t)nq * 16;                                  // the row's descriptor
+    int64_t end = 0;
+    if (which == PICOSPEC_CALL_COMPRESS) {
+        using G = CompressGeom<BF16>;
+        const int sub_elems = G::SUB_VECS * N, n_sub = (L + sub_elems - 1) / sub_elems;
+        for (int sub = 0; sub < n_sub + 2 * G::RING; ++sub)               // every sub-tile and every look-ahead position behind the row
+            for (int j = 0; j < G::SV; ++j)
+                for (int tid = 0; tid < kCompressThreads; ++tid)
+                    end = std::max(end, buffer_lane_read_end(size, (int64_t)G::group_first(sub, j) * 16, (int64_t)tid * 16));
+    } else {
+        using G = ResidualGeom<BF16>;
+        const int n_tiles = (L + kResidualTile - 1) / kResidualTile;
+        for (int it = 0; it < n_tiles + 2 * G::AHEAD; ++it)
+            for (int w = 0; w < kResidualThreads / 64; ++w)
+                for (int jv = 0; jv < G::NV; ++jv)
+                    for (int lane = 0; lane < 64; ++lane)
+                        end = std::max(end, buffer_lane_read_end(size, (int64_t)G::group_first(it, w, jv) * 16, (int64_t)lane * 16));
+    }
+    return end;
+}
 
 }  // namespace
 
@@ -317,6 +349,23 @@ size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t
 {
     (void)which_call; (void)dtype; (void)rows; (void)V; (void)k;
     return 0;   // every kernel keeps its intermediate state in LDS
+}
+
+int64_t picospec_max_load_byte(int which_call, int dtype, int32_t V, int32_t misalign_bytes)
+{
+    if (which_call != PICOSPEC_CALL_COMPRESS && which_call != PICOSPEC_CALL_SAMPLE_RESIDUAL) return -1;
+    if (dtype != PICOSPEC_F32 && dtype != PICOSPEC_BF16) return -1;
+    const int esz = dtype == PICOSPEC_F32 ? 4 : 2;
+    if (V < 1 || V > kMaxV || misalign_bytes < 0 || misalign_bytes > 15 || misalign_bytes % esz) return -1;
+    const int o = misalign_bytes / esz;
+    const int64_t end = dtype == PICOSPEC_BF16 ? max_load_end<true>(which_call, V, o) : max_load_end<false>(which_call, V, o);
+    return end - misalign_bytes;
+}
+
+int picospec_check_device(void* workspace, size_t workspace_bytes, uint32_t* status, void* stream)
+{
+    if (!workspace || !status || workspace_bytes < (size_t)kCheckBytes || ((uintptr_t)workspace & 15u)) return PICOSPEC_EINVAL;
+    return hip_status(launch_check_device(workspace, status, (hipStream_t)stream));
 }
 
 int64_t picospec_limit(int which)

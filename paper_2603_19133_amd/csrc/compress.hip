@@ -37,15 +37,13 @@
 
 #include "common.hpp"
 #include "kernels.hpp"
+#include "rowspan.hpp"
 
 namespace picospec {
 
 namespace {
 
-#ifndef PICOSPEC_COMPRESS_THREADS
-#define PICOSPEC_COMPRESS_THREADS 512
-#endif
-constexpr int kT = PICOSPEC_COMPRESS_THREADS;   // threads per workgroup
+constexpr int kT = kCompressThreads;        // threads per workgroup
 constexpr int kW = kT / kWave;
 constexpr int kCap = 8192;                  // candidate slots in LDS (value + id, 8 bytes)
 constexpr int kBinsLog2 = 11;
@@ -281,13 +279,7 @@ __device__ __forceinline__ void order_prepare(CompressShared& sh, int n) {
 //     its bin is the number of larger bin-mates, and the positions below k are kept.
 // A bin too crowded for that sends the row through the radix select and a sorting network.
 template <bool BF16>
-__device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi,
-                                                       unsigned long long* stamp_out) {
-#ifdef PICOSPEC_PHASE_CLOCKS
-#define OSTAMP(i) do { if (threadIdx.x == 0) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); stamp_out[i] = wall_clock64(); } } while (0)
-#else
-#define OSTAMP(i) do { (void)stamp_out; } while (0)
-#endif
+__device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     uint64_t* buf = reinterpret_cast<uint64_t*>(sh.cand_val);   // cand_val and cand_id, back to back
     const uint32_t kr = key_hi - key_lo;
@@ -312,7 +304,6 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();
-    OSTAMP(7);
     // fine bins per coarse range, in proportion to its count (at least one where there is a candidate); one
     // wave builds the table, kCoarse / 64 consecutive ranges per lane
     if (wave == 0) {
@@ -331,7 +322,6 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         for (int u = 0; u < kPerLane; ++u) { sh.coarse[lane * kPerLane + u] = (nf[u] << 16) | first; first += nf[u]; }
     }
     __syncthreads();
-    OSTAMP(8);
     int meta[kCandPer];                      // (fine bin << 16) | arrival order within the bin; -1: no candidate
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) {
@@ -345,7 +335,6 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();
-    OSTAMP(9);
     // exclusive prefix over the bins, in place; the bin that holds the k-th largest; the most crowded bin in front of it
     int h[kBinsPer], loc = 0;
 #pragma unroll
@@ -385,14 +374,12 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         bitonic_sort_desc(buf, P);
         return buf;
     }
-    OSTAMP(10);
     const int piv = sh.piv_bin, n_keep = sh.piv_before;
     // gather bin by bin (every candidate is in registers: the buffer may be overwritten)
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j)
         if (meta[j] >= 0 && (meta[j] >> 16) <= piv) buf[(int)sh.hist[meta[j] >> 16] + (meta[j] & 0xFFFF)] = c[j];
     __syncthreads();
-    OSTAMP(11);
     int pos[kCandPer];
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) {
@@ -413,7 +400,6 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
         }
     }
     __syncthreads();                         // all positions are known before the ordered list overwrites the bins
-    OSTAMP(12);
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j) if (pos[j] < k) buf[pos[j]] = c[j];
     __syncthreads();
@@ -443,14 +429,13 @@ __device__ __forceinline__ void compress_row(
     CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
     // A row is streamed in sub-tiles of SV 16-byte vectors per thread.  The sample from which the first
     // threshold is taken has the size of T0 sub-tiles (8192 elements) and is processed in one piece.
+    using Geom = CompressGeom<BF16>;
     constexpr int N = Vec<BF16>::N;
-    constexpr int SAMPLE = 8192;
-    constexpr int SV = (2 * kT * N <= SAMPLE) ? 2 : 1, ES = SV * N, SUB = kT * ES;
+    constexpr int SAMPLE = kCompressSample;
+    constexpr int SV = Geom::SV, ES = SV * N, SUB = kT * ES;
     constexpr int T0 = SAMPLE / SUB, NV0 = T0 * SV, E0 = NV0 * N;
-#ifndef PICOSPEC_COMPRESS_RING
-#define PICOSPEC_COMPRESS_RING 4
-#endif
-    constexpr int RING = PICOSPEC_COMPRESS_RING * (2 / SV);  // sub-tile buffers: one in use, the others in flight
+    constexpr int RING = Geom::RING;             // sub-tile buffers: one in use, the others in flight
+    static_assert(Geom::N == N, "vector width");
     static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: what is indexed by it is addressed from a scalar
@@ -461,17 +446,6 @@ __device__ __forceinline__ void compress_row(
         const int d0 = seq_off[row], g = max(seq_off[row + 1] - d0, 0);
         in_row = (int64_t)d0 + row + min(max(n_accept[row], 0), g);
     }
-    // Optional timeline (-DPICOSPEC_PHASE_CLOCKS, off in the library): thread 0 of every workgroup stores the
-    // 100 MHz wall clock at the phase boundaries, 16 words per row behind the prob array, which the caller
-    // of such a build must have allocated (python -m paper_2603_19133_amd.phase_clocks does).
-#ifdef PICOSPEC_PHASE_CLOCKS
-    unsigned long long* stamp_out = reinterpret_cast<unsigned long long*>(prob + (int64_t)n_rows * k) + row * 16;
-#define STAMP(i) do { if (threadIdx.x == 0) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); stamp_out[i] = wall_clock64(); } } while (0)
-#else
-    unsigned long long* stamp_out = nullptr;
-#define STAMP(i) do {} while (0)
-#endif
-    STAMP(0);
     const RowView rv = row_view<BF16>(logits, ld, in_row, V);
     const int n_sub = (rv.L + SUB - 1) / SUB;
     const int nq = (rv.L + N - 1) / N;           // 16-byte vectors that overlap the row
@@ -479,14 +453,17 @@ __device__ __forceinline__ void compress_row(
     const float qnan = __uint_as_float(0x7FC00000u);
 
     // Row loads go through a buffer descriptor that spans the row's nq vectors: the address is the
-    // descriptor's base + a scalar offset (sub-tile, vector) + this lane's constant offset, so that no
-    // vector arithmetic forms it, and vectors behind the row read as zero (unpack masks them anyway).
+    // descriptor's base + a scalar offset (sub-tile, vector group) + this lane's constant offset, so that no
+    // vector arithmetic forms it.  On gfx950 a raw buffer load (stride 0) compares scalar offset + lane
+    // offset + 16 with the descriptor's size (measured; picospec_check_device() tests it on the device at
+    // hand), so vectors behind the row read as zero without touching memory: the look-ahead loads behind
+    // the last sub-tile need no guard (rowspan.hpp states the rule; unpack masks the elements anyway).
     const __amdgpu_buffer_rsrc_t row_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)rv.base, 0, nq * 16, 0x00020000);
     const int lane_off = tid * 16;
     auto load_sub = [&](int sub, uint4 (&dst)[SV]) {
 #pragma unroll
         for (int j = 0; j < SV; ++j) {
-            const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(row_rsrc, lane_off, (sub * (kT * SV) + j * kT) * 16, 2 /* non-temporal */);
+            const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(row_rsrc, lane_off, Geom::group_first(sub, j) * 16, 2 /* non-temporal */);
             dst[j] = make_uint4(t.x, t.y, t.z, t.w);
         }
     };
@@ -727,13 +704,11 @@ __device__ __forceinline__ void compress_row(
             float bm;
             if (optimistic) {
                 unpack_sample(&rb[0][0], v);
-                STAMP(1);
                 bm = kNegInf;
 #pragma unroll
                 for (int e = 0; e < E0; ++e) bm = fmaxf(bm, v[e]);      // fmaxf skips the NaN of masked elements
             } else {
                 unpack_vecs(nv0_t{}, tid, &rb[0][0], v, true);
-                STAMP(1);
                 bm = add_stats(e0_t{}, v, true);
             }
             // smallest value of the sample; the optimistic pass leaves masked vocabulary entries (-inf) out of it,
@@ -763,7 +738,6 @@ __device__ __forceinline__ void compress_row(
             unsigned masked = 0;
 #pragma unroll
             for (int w = 0; w < kW; ++w) { key_hi = max(key_hi, sh.wkey[w]); key_lo = min(key_lo, sh.wkey[kW + w]); masked |= sh.wkey[2 * kW + w]; }
-            STAMP(2);
             bool have_tau = false;
             if (one_pass) {
                 // Optimistic pass: the threshold only has to be about right (the count at the end of the row
@@ -798,7 +772,6 @@ __device__ __forceinline__ void compress_row(
                         }
                     }
                     __syncthreads();             // (the histogram and the pivot words are reused below)
-                    STAMP(3);
                 } else if (masked && !(vmax > vmin) && vmax < __builtin_huge_valf()) {
                     // masked entries and at most one value above -inf in the whole sample (a vocabulary mask that
                     // leaves a handful of ids): every entry above -inf becomes a candidate
@@ -845,12 +818,11 @@ __device__ __forceinline__ void compress_row(
             }
         }
 
-        STAMP(4);
         bool enough = true;
         if (optimistic) {
             // ---- the row from its start, optimistic: waves run free; a reservation that does not fit gives the
             //      pass up.  The ring buffers rotate by role (no copies): while one sub-tile is processed
-            //      three are in flight; loads behind the row are clamped, so they need no guard.
+            //      three are in flight; loads behind the row read zero without touching memory (load_sub).
             const bool applies = !admit_all;     // a sample without a threshold (rows of -inf) leaves the row to the safe pass
             if (applies) {
 #pragma unroll
@@ -957,7 +929,6 @@ __device__ __forceinline__ void compress_row(
         if (!enough) continue;                   // optimistic threshold too high, or buffer full: stream again, safely
 
         // ---- end of row
-        STAMP(5);
         if (n_held < 0) n_held = sh.cnt;
         order_prepare(sh, n_held);               // (the barriers of the combine below stand behind it)
         {   // M = max over the threads; S = sum s * 2^(r - M*c), combined in fp64
@@ -981,7 +952,6 @@ __device__ __forceinline__ void compress_row(
             }
         }
         key_hi = short_key<BF16>(__float_as_uint(M));
-        STAMP(6);
         break;
     }
 
@@ -1005,8 +975,7 @@ __device__ __forceinline__ void compress_row(
 
     // ---- exact cut to k, ordering and emission
     const int n = min(n_held, k);
-    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, n, V, key_lo, key_hi, stamp_out);
-    STAMP(13);
+    const uint64_t* sorted = order_top_k<BF16>(sh, n_held, n, V, key_lo, key_hi);
 
     // A mostly masked row with fewer entries above -inf than k (all of them are held): the record goes on with
     // masked entries (probability 0), lowest ids first, i.e. with the lowest ids that are not held.  There are
@@ -1135,7 +1104,6 @@ __device__ __forceinline__ void compress_row(
             if (keep) { my_mass += (double)pr; ++my_count; }
         }
     }
-    STAMP(14);
     const double wm = wave_sum(my_mass);
     const int wc = wave_sum(my_count);
     if (lane == 0) { sh.red[wave] = wm; sh.red[kW + wave] = (double)wc; }
@@ -1146,7 +1114,6 @@ __device__ __forceinline__ void compress_row(
         mass[row] = (float)tm;
         count[row] = (int)tc;
     }
-    STAMP(15);
 }
 
 template <bool BF16>
@@ -1298,8 +1265,8 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
                            float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream)
 {
-    static bool limit_raised[2][kMaxDevices] = {};
-    static int resident[kMaxDevices] = {};       // rows resident at a time (2 workgroups per CU): the distance of the look-ahead loads
+    static DeviceFlags limit_raised[2] = {};
+    static std::atomic<int> resident[kMaxDevices] = {};   // rows resident at a time (2 workgroups per CU): the distance of the look-ahead loads
     const size_t smem = sizeof(CompressShared);
     auto f32 = compress_kernel<false>;
     auto b16 = compress_kernel<true>;
@@ -1312,11 +1279,13 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
     if (n_rows == 0) return hipSuccess;
     int ahead = 0;
     if (!seq_off) {                              // (no look-ahead with a row map: the next row is not known from the row number)
-        if (resident[dev] == 0) {
+        int res = resident[dev].load(std::memory_order_relaxed);
+        if (res == 0) {                          // (first use on this device; a second thread here computes the same value)
             int cus = 0;
-            resident[dev] = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? 2 * cus : -1;
+            res = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? 2 * cus : -1;
+            resident[dev].store(res, std::memory_order_relaxed);
         }
-        ahead = resident[dev] > 0 ? resident[dev] : 0;
+        ahead = res > 0 ? res : 0;
     }
     const float inv_T = 1.0f / temperature;
     if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
@@ -1329,7 +1298,7 @@ hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d
                                const void* tgt_logits, int64_t ld_t, int n_target,
                                float* tgt_max, float* tgt_sum, float* tgt_lse, hipStream_t stream)
 {
-    static bool limit_raised[2][kMaxDevices] = {};
+    static DeviceFlags limit_raised[2] = {};
     const size_t smem = sizeof(CompressShared);
     auto f32 = round_stream_kernel<false>;
     auto b16 = round_stream_kernel<true>;

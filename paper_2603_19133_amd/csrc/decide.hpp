@@ -6,6 +6,7 @@
 
 #include "common.hpp"
 #include "kernels.hpp"
+#include "rowspan.hpp"
 
 namespace picospec {
 
@@ -118,8 +119,9 @@ __device__ __forceinline__ int accept_sequence(
             double p = 0.0;
             if (!bad) p = exp_emit(z_t, M_t, cd) / (double)S_t;
             const double u = (double)u_t;
-            // u < min(1, p/qhat), without forming the quotient; qhat = 0 counts as ratio = +inf
-            const bool accept = (u < 1.0) && (qh > 0.0 ? (u * qh < p) : true);
+            // u < min(1, p/qhat), without forming the quotient; qhat = 0 counts as ratio = +inf.  An id outside the
+            // vocabulary has p = 0 whatever qhat is said to be: it is rejected, so the accepted prefix ends in front of it
+            const bool accept = !bad && (u < 1.0) && (qh > 0.0 ? (u * qh < p) : true);
             if (!accept) atomicMin(&s_first, i);
             if (p_tok) p_tok[rd] = (float)p;
             if (q_tok) q_tok[rd] = (float)qh;
@@ -136,7 +138,8 @@ __device__ __forceinline__ int accept_sequence(
 }
 
 
-constexpr int kTile = 16384;                                  // elements per tile (both dtypes)
+constexpr int kTile = kResidualTile;                          // elements per tile (both dtypes)
+static_assert(kResidualThreads == kThreads, "one workgroup of kThreads threads per sequence");
 constexpr int kSegLen = kTile / kWaves;                       // 1024 consecutive ids per wave and tile
 constexpr int kMaxTiles = (kMaxV + 16) / kTile + 1;
 constexpr int kMaxSeg = kMaxTiles * kWaves;
@@ -164,8 +167,10 @@ __device__ __forceinline__ void residual_sequence(
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     ResidualShared& sh = *reinterpret_cast<ResidualShared*>(smem_raw);
-    constexpr int N = Vec<BF16>::N, NV = kTile / (kThreads * N);      // vectors per thread and tile
-    constexpr int kSegVec = NV * kWave;                                // vectors per segment
+    using Geom = ResidualGeom<BF16>;
+    constexpr int N = Vec<BF16>::N, NV = Geom::NV;                     // vectors per thread and tile
+    constexpr int kSegVec = Geom::SEG_VECS;                            // vectors per segment
+    static_assert(Geom::TILE_VECS == kThreads * NV && kSegVec == NV * kWave, "tile geometry");
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: it forms scalar load offsets
     const int d0 = seq_off[b];
@@ -192,8 +197,9 @@ __device__ __forceinline__ void residual_sequence(
     const int32_t* ids = q_idx + rd * k;
     const float* qp = q_prob + rd * k;
     const int nq = (rv.L + N - 1) / N;
-    // row loads: descriptor base + scalar offset of the vector group + this lane's offset; vectors
-    // behind the row read as zero and are masked
+    // row loads: descriptor base + scalar offset of the vector group + this lane's offset.  On gfx950 a raw
+    // buffer load compares scalar offset + lane offset + 16 with the descriptor's size (measured;
+    // picospec_check_device() tests it), so vectors behind the row read as zero without touching memory
     const __amdgpu_buffer_rsrc_t row_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)rv.base, 0, nq * 16, 0x00020000);
     // vector `first + lane` of the row (first is uniform across the wave)
     auto load_vec = [&](int first) {
@@ -260,7 +266,7 @@ __device__ __forceinline__ void residual_sequence(
         uint4 tb[3][NV];
         auto load_tile = [&](int it, uint4 (&dst)[NV]) {
 #pragma unroll
-            for (int jv = 0; jv < NV; ++jv) dst[jv] = load_vec(it * (kThreads * NV) + wave_vec + jv * kWave);
+            for (int jv = 0; jv < NV; ++jv) dst[jv] = load_vec(Geom::group_first(it, wave, jv));
         };
         load_tile(0, tb[0]);
         load_tile(1, tb[1]);
@@ -341,9 +347,9 @@ __device__ __forceinline__ void residual_sequence(
     if (my_pick != 0x7FFFFFFF) atomicMin(&sh.seg_pick, my_pick);
     if (my_last >= 0) atomicMax(&sh.seg_last, my_last);
     __syncthreads();
-    int pick = sh.seg_pick;
+    int pick = __builtin_amdgcn_readfirstlane(sh.seg_pick);   // (uniform: it forms scalar load offsets below)
     const bool crossed = pick != 0x7FFFFFFF;
-    if (!crossed) pick = sh.seg_last < 0 ? 0 : sh.seg_last;   // rounding: last segment with mass
+    if (!crossed) pick = max(__builtin_amdgcn_readfirstlane(sh.seg_last), 0);   // rounding: last segment with mass
     if (crossed && my_pick == pick) sh.before = cum;          // exactly one thread owns the chosen segment
     // (both images are empty again: every entry was taken back after its tile)
     const int pt = pick / kWaves, pw = pick % kWaves;
@@ -361,7 +367,7 @@ __device__ __forceinline__ void residual_sequence(
         for (int jv = 0; jv < NV; ++jv) {
             float r[N];
             const int ql = jv * kWave + lane;
-            residual_of(load_vec(seg_vec + jv * kWave), seg_vec + ql, sh.qimg[0] + ql * N, true, r);
+            residual_of(load_vec(Geom::group_first(pt, pw, jv)), seg_vec + ql, sh.qimg[0] + ql * N, true, r);
             double sum = 0.0;
 #pragma unroll
             for (int e = 0; e < N; ++e) sum += (double)r[e];

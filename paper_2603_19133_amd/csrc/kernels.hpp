@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace picospec {
 
 constexpr int kMaxK = 4096;          // candidate buffer in LDS holds 16384 entries; k beyond this is refused
@@ -15,15 +17,18 @@ constexpr int kRoundSmallRows = 512;
 
 // Kernels whose dynamic LDS exceeds the 64 KB default need their limit raised once per device and kernel.
 // `done` is the caller's per-device record for that kernel; the current device's ordinal comes back in `dev`.
+// The record is atomic and the attribute call idempotent: two threads that meet here on a kernel's first use
+// both set the same value, and a thread that reads `true` (acquire) finds the attribute set.
 constexpr int kMaxDevices = 64;
-inline hipError_t raise_lds_limit_once(const void* kernel, size_t bytes, bool (&done)[kMaxDevices], int& dev) {
+using DeviceFlags = std::atomic<bool>[kMaxDevices];
+inline hipError_t raise_lds_limit_once(const void* kernel, size_t bytes, DeviceFlags& done, int& dev) {
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    if (!done[dev]) {
+    if (!done[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
         if (e != hipSuccess) return e;
-        done[dev] = true;
+        done[dev].store(true, std::memory_order_release);
     }
     return hipSuccess;
 }
@@ -82,6 +87,10 @@ hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t l
                                   const int32_t* p_idx, const float* p_prob, const int32_t* p_count, const float* p_mass,
                                   int k, int renorm, const float* uniforms,
                                   int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
+
+// device self-check of the buffer loads' range check (csrc/selfcheck.hip); the workspace holds kCheckBytes
+constexpr int kCheckBytes = 64 * 1024;
+hipError_t launch_check_device(void* workspace, uint32_t* status, hipStream_t stream);
 
 // ---- wire messages (csrc/wire.hip); fmt: 0 fp32, 1 fp16, 2 bf16 probabilities
 int64_t downlink_bytes_max(int B, int k, int fmt);

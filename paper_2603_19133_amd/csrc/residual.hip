@@ -58,7 +58,7 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            int k, int renorm, const float* uniforms,
                            int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream)
 {
-    static bool limit_raised[2][kMaxDevices] = {};
+    static DeviceFlags limit_raised[2] = {};
     const size_t smem = sizeof(ResidualShared);
     auto f32 = residual_kernel<false>;
     auto b16 = residual_kernel<true>;
@@ -82,7 +82,7 @@ hipError_t launch_decide(const void* tgt_logits, int dtype, int64_t ld, int V, f
                          int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
                          int32_t* out_tok, float* resid_mass, uint32_t* res_flags, hipStream_t stream)
 {
-    static bool limit_raised[2][kMaxDevices] = {};
+    static DeviceFlags limit_raised[2] = {};
     const size_t smem = sizeof(ResidualShared);
     auto f32 = decide_kernel<false>;
     auto b16 = decide_kernel<true>;

@@ -7,7 +7,13 @@ Match criteria (written here once, used by every parity test):
     within ACCEPT_MARGIN (relative) of p/q, a draw whose u*R lies within CDF_MARGIN (relative to R)
     of a CDF step, a top-p count whose threshold lies within TOPP_MARGIN of a cumulative sum.
     Those sequences/rows are listed, excluded, and their number is bounded.
-  * probabilities, masses, log-sum-exps: relative RTOL.
+  * probabilities, masses (the residual mass included), log-sum-exps: relative RTOL, no absolute term.
+
+This is the default (`strict=True`) and what every test on the five benchmark workloads, the smoke run and the
+full-size rounds assert.  Only the seeded random sweep, whose rounds include peaked and identical rows by design,
+passes `strict=False`: a sequence whose ORACLE residual mass lies below PEAKED_R then gets the absolute term
+RESID_ATOL on the residual mass and on the position of u*R (the reason is written at RESID_ATOL); sequences with a
+larger residual mass are held to the strict criteria there as well.
 """
 from __future__ import annotations
 
@@ -27,9 +33,13 @@ CDF_MARGIN = 1e-6
 TOPP_MARGIN = 1e-6
 # The residual mass is a sum of differences P(x) - qhat(x) of fp32 probabilities in [0, 1] (the record of Eq. 4
 # stores fp32 values; P is formed with one fp32 exponential), each known to about 2^-23 of its own size: where one
-# token carries almost all of the mass on both sides, R is small and its error is absolute, a few 1e-7, not
-# relative to R.  The same holds for the position of u*R on the residual CDF.
+# token carries almost all of the mass on both sides, R is small and its error is absolute, up to 2 * 2^-23 * p_max
+# = 2.4e-7, not relative to R.  RTOL * R covers that as long as R >= 2.4e-7 / RTOL = 0.024; the absolute term below
+# is applied (strict=False only) to sequences whose oracle residual mass is smaller than PEAKED_R = 0.01, i.e. where
+# the draft and the target all but coincide on a dominant token.  The same holds for the position of u*R on the
+# residual CDF.
 RESID_ATOL = 1e-6
+PEAKED_R = 1e-2
 
 
 def to_device(a: np.ndarray, device) -> torch.Tensor:
@@ -122,11 +132,17 @@ def compare_compress(g: ps.Compressed, o: oracle.Compressed, top_p: float = 0.0)
     return dict(prob=e_prob, mass=e_mass, lse=e_lse, topp_excluded=excluded)
 
 
-def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: float = 0.02) -> dict:
+def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: float = 0.02,
+                  strict: bool = True) -> dict:
     w = r.workload
     st = compare_compress(g.q, o.q, w.top_p)
-    assert not st["topp_excluded"] or True
     off, B = r.seq_off, r.B
+    # absolute term of the residual mass, per sequence: none, except (strict=False) where the oracle's residual mass
+    # says that one dominant token all but cancels
+    if strict:
+        atol_b = np.zeros(B)
+    else:
+        atol_b = np.where(o.res.resid_mass < PEAKED_R, RESID_ATOL, 0.0)
     # target statistics
     lse_g = n(g.ver.tgt_max).astype(np.float64) / w.T + np.log(n(g.ver.tgt_sum).astype(np.float64))
     st["tgt_lse"] = assert_close(lse_g, o.ver.tgt_lse, RTOL_LSE, "tgt_lse (from max,sum)", atol=1e-6)
@@ -151,14 +167,15 @@ def compare_round(g: GpuRound, o: OracleRound, r: W.Round, max_excluded_frac: fl
     # u*R lies within CDF_MARGIN (relative to R) of a step of the oracle's CDF
     tok_g = n(g.res.out_tok)
     tok_same = tok_g == o.res.out_tok
-    # (a residual mass within RESID_ATOL of zero: whether it counts as empty is not decidable in fp32)
-    undecided = o.res.resid_mass <= RESID_ATOL       # (the oracle reports 0 for an empty residual)
-    tok_allowed = (o.res.cdf_margin < CDF_MARGIN + RESID_ATOL / np.maximum(o.res.resid_mass, 1e-300)) | undecided | tainted
+    # (strict=False: a residual mass within RESID_ATOL of zero: whether it counts as empty is not decidable in fp32;
+    #  the oracle reports 0 for an empty residual)
+    undecided = (o.res.resid_mass <= RESID_ATOL) if not strict else np.zeros(B, bool)
+    tok_allowed = (o.res.cdf_margin < CDF_MARGIN + atol_b / np.maximum(o.res.resid_mass, 1e-300)) | undecided | tainted
     assert (tok_same | tok_allowed | ~same).all(), \
         ("out_tok", np.nonzero(same & ~tok_same & ~tok_allowed)[0][:10])
     # (a sequence with a record on the top-p knife edge may draw against a record one entry longer or shorter)
     clean = same & ~tainted
-    st["resid_mass"] = assert_close(n(g.res.resid_mass)[clean], o.res.resid_mass[clean], RTOL, "resid_mass", atol=RESID_ATOL)
+    st["resid_mass"] = assert_close(n(g.res.resid_mass)[clean], o.res.resid_mass[clean], RTOL, "resid_mass", atol=atol_b[clean])
     assert ((n(g.res.flags).astype(np.int64) & 0xFFFFFFFF)[clean & ~undecided] == o.res.flags[clean & ~undecided]).all(), "residual flags"
     st["mismatch_accept"] = int((~same).sum())           # all of them knife-edge (asserted above)
     st["mismatch_draw"] = int((same & ~tok_same & ~undecided & ~tainted).sum())  # all of them within CDF_MARGIN of a step

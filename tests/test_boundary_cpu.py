@@ -271,3 +271,32 @@ def test_compress_kernels_keep_everything_in_registers():
     kernels = {k: v for k, v in spills.items() if "compress_kernel" in k}
     assert len(kernels) == 2, spills
     assert all(v == 0 for v in kernels.values()), kernels
+
+
+def test_streaming_loads_stay_inside_the_row(B):
+    """The row loads of the compress and residual kernels, look-ahead included, never address a byte behind the aligned
+    16-byte block that holds the row's last byte, whatever the row length and its alignment: the library's own
+    addressing rule (the functions the kernels use), evaluated over every lane on the host."""
+    sizes = [1, 2, 3, 7, 8, 9, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1000, 2047, 2048, 2049, 4095, 4096, 4097,
+             8191, 8192, 8193, 16383, 16384, 16385, 16400, 32000, 32767, 32768, 32769, 65535, 65537, 128256, 151936,
+             152064, (1 << 20) - 1, 1 << 20]
+    for which in (B.CALL_COMPRESS, B.CALL_SAMPLE_RESIDUAL):
+        for dtype, esz in ((B.F32, 4), (B.BF16, 2)):
+            for V in sizes:
+                for mis in range(0, 16, esz):
+                    end = B.max_load_byte(which, dtype, V, mis)
+                    row_bytes = V * esz
+                    allowed = (mis + row_bytes + 15) // 16 * 16 - mis      # end of the last byte's aligned block
+                    assert row_bytes - 15 <= end <= allowed, (which, dtype, V, mis, end, allowed)
+    assert B.max_load_byte(B.CALL_VERIFY, B.F32, 100, 0) == -1
+    assert B.max_load_byte(B.CALL_COMPRESS, B.BF16, 100, 3) == -1
+    assert B.max_load_byte(B.CALL_COMPRESS, B.F32, 0, 0) == -1
+    assert B.max_load_byte(B.CALL_COMPRESS, B.F32, (1 << 20) + 1, 0) == -1
+
+
+def test_check_device_rejects_misuse(B):
+    f = B.lib.picospec_check_device
+    assert f(None, 1 << 16, FAKE, None) == B.EINVAL
+    assert f(FAKE, 1 << 16, None, None) == B.EINVAL
+    assert f(FAKE, (1 << 16) - 1, FAKE, None) == B.EINVAL          # workspace too small
+    assert f(FAKE + 4, 1 << 16, FAKE, None) == B.EINVAL             # not on a 16-byte boundary

@@ -27,7 +27,7 @@ def _announce(*a):
     print("[case]", *a, flush=True)
 
 
-def _downlink(pu, ps, gpu, r, k, renorm, n_accept=None, top_p=0.0):
+def _downlink(pu, ps, gpu, r, k, renorm, n_accept=None, top_p=0.0, strict=True):
     """Oracle and library on one round: verify with the scalar uplink, record of the rejected row, local resampling."""
     w = r.workload
     # the drafter's tokens and scalar q_i (edge side: dense draft distribution, here through a full-support record)
@@ -52,13 +52,15 @@ def _downlink(pu, ps, gpu, r, k, renorm, n_accept=None, top_p=0.0):
     if r.N:
         olse = oracle.compress(r.draft_logits, w.V, w.T, 1).lse
         pu.assert_close(pu.n(dlse), olse, pu.RTOL_LSE, "draft lse", atol=2e-6)
-    # a residual mass within the arithmetic's absolute error of zero: whether it counts as empty (flag, fallback
-    # draw from the record) is not decidable in fp32 -- in exact arithmetic such a position is never rejected
-    undecided = ores.resid_mass <= pu.RESID_ATOL
+    # strict: relative tolerance only.  Otherwise (rounds with peaked or identical rows) a sequence whose ORACLE residual
+    # mass lies below PEAKED_R carries the absolute term RESID_ATOL, and a residual mass within it of zero is not
+    # compared for emptiness (flag, fallback draw from the record): in exact arithmetic such a position is never rejected
+    atol_b = np.zeros(r.B) if strict else np.where(ores.resid_mass < pu.PEAKED_R, pu.RESID_ATOL, 0.0)
+    undecided = np.zeros(r.B, bool) if strict else ores.resid_mass <= pu.RESID_ATOL
     assert (pu.n(gres.flags).astype(np.uint32) == ores.flags)[~undecided].all()
-    st["resid_mass"] = pu.assert_close(pu.n(gres.resid_mass), ores.resid_mass, pu.RTOL, "resid_mass", atol=pu.RESID_ATOL)
+    st["resid_mass"] = pu.assert_close(pu.n(gres.resid_mass), ores.resid_mass, pu.RTOL, "resid_mass", atol=atol_b)
     same = pu.n(gres.out_tok) == ores.out_tok
-    knife = (ores.cdf_margin < pu.CDF_MARGIN + pu.RESID_ATOL / np.maximum(ores.resid_mass, 1e-300)) | undecided
+    knife = (ores.cdf_margin < pu.CDF_MARGIN + atol_b / np.maximum(ores.resid_mass, 1e-300)) | undecided
     excl = set(st["topp_excluded"])
     for b in np.nonzero(~same)[0]:
         assert knife[b] or b in excl, (b, pu.n(gres.out_tok)[b], ores.out_tok[b], ores.cdf_margin[b])
@@ -109,7 +111,7 @@ def test_downlink_small_ragged_every_position(gpu, pu, ps, dtype):
         for shift in range(0, 6):
             na = np.minimum(g, shift).astype(np.int32)
             for renorm in (0, 1):
-                _downlink(pu, ps, gpu, r, k, renorm, n_accept=na)
+                _downlink(pu, ps, gpu, r, k, renorm, n_accept=na, strict=False)
 
 
 def test_downlink_empty_residual_and_bad_inputs(gpu, pu, ps):

@@ -368,7 +368,8 @@ def test_round_at_extreme_temperatures(gpu, pu, T, spread, dtype):
     r = _custom_round(w, draft, tgt, off, rng.random(N + B, dtype=np.float32), rng.random(N, dtype=np.float32))
     o = pu.oracle_round(r)
     gq = pu.gpu_round(r, o.tok, gpu)
-    pu.compare_round(gq, o, r, max_excluded_frac=0.34)
+    # (peaked by construction: sequences whose oracle residual mass lies below PEAKED_R carry the absolute term)
+    pu.compare_round(gq, o, r, max_excluded_frac=0.34, strict=False)
 
 
 def test_scalar_q_uplink_and_foreign_tokens(gpu, pu, ps):
@@ -492,13 +493,28 @@ def test_bad_inputs_are_flagged_not_fatal(gpu, pu, ps):
     tok[1] = w.V + 5          # token id outside the vocabulary
     g = pu.gpu_round(r, tok, gpu)
     assert pu.n(g.ver.flags)[0] & ps.FLAG_BAD_INPUT
+    # an id outside the vocabulary has p = 0: the accepted prefix ends in front of it, with the record's lookup and
+    # with the scalar uplink alike
+    assert pu.n(g.ver.n_accept)[0] == min(int(o.ver.n_accept[0]), 1) and pu.n(g.ver.p_tok)[1] == 0.0
     dev = lambda a: pu.to_device(a, gpu)
+    qs = torch.full((r.N,), 1e-9, dtype=torch.float32, device=gpu)    # q so small that every valid token is accepted
+    vs = ps.verify(dev(r.tgt_logits), w.V, w.T, dev(r.seq_off), r.N, dev(tok), None, dev(r.uniforms), q_scalar=qs)
+    torch.cuda.synchronize()
+    assert pu.n(vs.n_accept)[0] == 1 and pu.n(vs.flags)[0] & ps.FLAG_BAD_INPUT
     bad_n = dev(np.array([99], np.int32))   # n_accept outside [0, gamma]
     res = ps.sample_residual(dev(r.tgt_logits), w.V, w.T, dev(r.seq_off), r.N, g.ver, g.q, dev(r.uniforms),
                              n_accept=bad_n)
     torch.cuda.synchronize()
     assert pu.n(res.flags)[0] & ps.FLAG_BAD_INPUT
     assert 0 <= pu.n(res.out_tok)[0] < w.V
+
+
+def test_device_range_checks_buffer_loads_as_the_row_kernels_assume(gpu, ps):
+    """The memory safety of the look-ahead row loads rests on the range check of raw buffer loads taking the
+    scalar offset into account; the library's self-check probes that on this device (all probe addresses lie
+    inside its workspace)."""
+    _announce("device self-check")
+    assert ps.check_device(gpu) == 0
 
 
 def test_empty_batch(gpu, ps):
@@ -515,19 +531,24 @@ def test_empty_batch(gpu, ps):
 
 # ---------------------------------------------------------------- full-size rounds, sampled sequences
 
-FULL_CASES = [("cfg3", 0, 8), ("cfg4", 0, 6), ("cfg5", 0, 6), ("cfg5", 1, 4), ("cfg5", 50, 4), ("cfg5", 99, 6)]
+# (cfg3 and cfg4, the configuration the throughput is quoted on: every sequence; cfg5: 64 of the 512 per round)
+FULL_CASES = [("cfg3", 0, 64), ("cfg4", 0, 256), ("cfg5", 0, 64), ("cfg5", 1, 64), ("cfg5", 50, 64), ("cfg5", 99, 64)]
 
 
 @pytest.mark.parametrize("name,rnd,n_sample", FULL_CASES)
 def test_full_size_round_sampled_sequences(gpu, pu, ps, name, rnd, n_sample):
     """The whole batch at its real size goes through the library exactly as bench.py launches it (same calls,
-    same shapes); a seeded sample of sequences is checked element by element against the oracle, which
-    regenerates just those sequences.  Everything else is checked through size-independent properties."""
+    same shapes); the sequences of a seeded sample (all of them where n_sample is the batch size) are checked
+    element by element against the oracle under the strict criteria, and every row and sequence of the batch
+    through size-independent properties."""
     w = W.WORKLOADS[name]
     _announce("full size", name, "round", rnd, "B", w.B, "V", w.V, "k", w.k, w.dtype)
     full = W.build_round(w, rnd)
-    pick = np.sort(np.random.default_rng(1000 + rnd).choice(w.B, size=n_sample, replace=False))
-    sub = W.build_round(w, rnd, seqs=pick)
+    if n_sample >= w.B:
+        pick, sub = np.arange(w.B), full
+    else:
+        pick = np.sort(np.random.default_rng(1000 + rnd).choice(w.B, size=n_sample, replace=False))
+        sub = W.build_round(w, rnd, seqs=pick)
     o = pu.oracle_round(sub)
     dev = lambda a: pu.to_device(a, gpu)
     draft, tgt = dev(full.draft_logits), dev(full.tgt_logits)
@@ -543,7 +564,7 @@ def test_full_size_round_sampled_sequences(gpu, pu, ps, name, rnd, n_sample):
     res = ps.sample_residual(tgt, w.V, w.T, seq_off, full.N, ver, q, uni)
     torch.cuda.synchronize()
     g = pu.GpuRound(q, ver, res)
-    st = pu.compare_round(pu.slice_gpu_round(g, full, sub), o, sub, max_excluded_frac=0.2)
+    st = pu.compare_round(pu.slice_gpu_round(g, full, sub), o, sub, max_excluded_frac=0.05)
     print("[stats]", name, rnd, {k: v for k, v in st.items() if k != "topp_excluded"}, flush=True)
     # properties that hold for every row and sequence of the batch
     idx, prob, cnt, mass = pu.n(q.idx), pu.n(q.prob), pu.n(q.count), pu.n(q.mass)
