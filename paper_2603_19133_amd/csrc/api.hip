@@ -46,12 +46,16 @@ int64_t max_load_end(int which, int V, int o)
     const int64_t size = (int64_t)nq * 16;                                  // the row's descriptor
     int64_t end = 0;
     if (which == PICOSPEC_CALL_COMPRESS) {
-        using G = CompressGeom<BF16>;
-        const int sub_elems = G::SUB_VECS * N, n_sub = (L + sub_elems - 1) / sub_elems;
-        for (int sub = 0; sub < n_sub + 2 * G::RING; ++sub)               // every sub-tile and every look-ahead position behind the row
-            for (int j = 0; j < G::SV; ++j)
-                for (int tid = 0; tid < kCompressThreads; ++tid)
-                    end = std::max(end, buffer_lane_read_end(size, (int64_t)G::group_first(sub, j) * 16, (int64_t)tid * 16));
+        auto sweep = [&](auto geom) {                                       // both variants of the kernel
+            using G = decltype(geom);
+            const int sub_elems = G::SUB_VECS * N, n_sub = (L + sub_elems - 1) / sub_elems;
+            for (int sub = 0; sub < n_sub + 2 * G::RING; ++sub)           // every sub-tile and every look-ahead position behind the row
+                for (int j = 0; j < G::SV; ++j)
+                    for (int tid = 0; tid < kCompressThreads; ++tid)
+                        end = std::max(end, buffer_lane_read_end(size, (int64_t)G::group_first(sub, j) * 16, (int64_t)tid * 16));
+        };
+        sweep(CompressGeom<BF16, false>{});
+        sweep(CompressGeom<BF16, true>{});
     } else {
         using G = ResidualGeom<BF16>;
         const int n_tiles = (L + kResidualTile - 1) / kResidualTile;

@@ -10,7 +10,7 @@
 //     with at least r of the sample's elements at or above it.
 //   * Optimistic pass: the sample is 256 runs of 128 bytes spread evenly over the row (logits trend with
 //     the vocabulary id, so the head of a row would misplace the threshold); it is only looked at.  r is
-//     chosen so that about k + 4.5 sqrt(k) + 20 elements of the whole row are expected at or above the
+//     chosen (optimistic_rank, kernels.hpp) so that the row is expected to hold k plus a safety margin at or above the
 //     threshold.  The row is then streamed from its start: every element at or above the threshold
 //     claims a slot of the candidate buffer in LDS with an atomic of its own and writes (value, id)
 //     there; the softmax arithmetic sits between claim and write.  If the row ends with at least k
@@ -45,27 +45,30 @@ namespace {
 
 constexpr int kT = kCompressThreads;        // threads per workgroup
 constexpr int kW = kT / kWave;
-constexpr int kCap = 8192;                  // candidate slots in LDS (value + id, 8 bytes)
+constexpr int kRetryRow = -2;               // count of a row that the small variant leaves to the general kernel
+constexpr int kCapBig = 8192;               // candidate slots in LDS (value + id, 8 bytes): records of up to kMaxK entries
+constexpr int kCapSmall = 5120;             // ... and the variant for records of up to kMaxK / 2: three workgroups per CU
 constexpr int kBinsLog2 = 11;
 constexpr int kBins = 1 << kBinsLog2;       // histogram bins of the radix selects / rank sort
 constexpr int kBinsPer = kBins / kT;
 constexpr int kIdBits = 20;                 // ids < 2^20 (kMaxV)
 constexpr unsigned kIdMask = (1u << kIdBits) - 1u;
 constexpr int kSortMaxBin = 128;            // beyond this bin size the ordering falls back to a sorting network
-constexpr int kSortPer = kMaxK / kT;
-constexpr int kCandPer = kCap / kT;
 constexpr int kCoarseLog2 = 8;
 constexpr int kCoarse = 1 << kCoarseLog2;   // coarse ranges that steer the fine bins of the rank sort
 
-static_assert(kMaxK <= kCap && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
-static_assert((kCap & (kCap - 1)) == 0, "slots wrap around the buffer by masking");
-static_assert(kCap < 65536 && kBins <= 32768, "bin and arrival order of a candidate share one register");
+static_assert(kMaxK <= kCapBig && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
+static_assert(kBins <= 32768, "bin and arrival order of a candidate share one register");
 static_assert(kMaxV <= (1 << kIdBits), "id field of the composite key");
-static_assert(kCap <= 65536 && kCap / 2 * 2 <= kBins * 4, "a prune keeps a 16-bit index list in the histogram");
 
+template <int CAP>
 struct __align__(16) CompressShared {
-    unsigned cand_val[kCap];                // candidates: fp32 bit pattern ...
-    unsigned cand_id[kCap];                 // ... and vocabulary id (the sort reuses both arrays as uint64 regions)
+    static constexpr int kCap = CAP;        // candidate slots
+    static constexpr int kRecMax = CAP >= 2 * kMaxK ? kMaxK : kMaxK / 2;   // longest record this buffer serves
+    static_assert(CAP % (2 * kT) == 0 && CAP < 65536, "whole slots per thread; a prune keeps a 16-bit index list");
+    static_assert(kRecMax <= kBins * 2 && kRecMax <= CAP, "a prune's 16-bit index list (one entry per kept slot) lives in the histogram");
+    unsigned cand_val[CAP];                 // candidates: fp32 bit pattern ...
+    unsigned cand_id[CAP];                  // ... and vocabulary id (the sort reuses both arrays as uint64 regions)
     unsigned hist[kBins];
     unsigned coarse[kCoarse];               // rank sort: count, then (fine bins << 16) | first fine bin, per coarse range
     double red[2 * kW];
@@ -80,7 +83,8 @@ struct __align__(16) CompressShared {
     int epoch_valid[3];                     // safe pass, per attempt epoch: first reservation that did not fit
 };
 
-static_assert(sizeof(CompressShared) <= 80 * 1024, "two workgroups share the 160 KB of LDS of a gfx950 CU");
+static_assert(sizeof(CompressShared<kCapBig>) <= 80 * 1024, "two workgroups share the 160 KB of LDS of a gfx950 CU");
+static_assert(sizeof(CompressShared<kCapSmall>) <= 160 * 1024 / 3, "three workgroups of the small variant share a CU's LDS");
 
 template <bool BF16>
 __device__ __forceinline__ uint32_t short_key(uint32_t bits) {
@@ -102,7 +106,8 @@ __device__ __forceinline__ uint64_t composite(uint32_t bits, uint32_t id) {
     return ((uint64_t)short_key<BF16>(bits) << kIdBits) | (uint64_t)(kIdMask - id);
 }
 
-__device__ __forceinline__ void zero_hist(CompressShared& sh) {
+template <class SH>
+__device__ __forceinline__ void zero_hist(SH& sh) {
 #pragma unroll
     for (int j = 0; j < kBinsPer; ++j) sh.hist[threadIdx.x + j * kT] = 0;
 }
@@ -111,7 +116,8 @@ __device__ __forceinline__ void zero_hist(CompressShared& sh) {
 // bin in which the running count first reaches `need`.  Broadcasts its index, the count in front of
 // it and its own count through sh.piv_*; read them after the call.  Returns the total count.  A histogram
 // that holds fewer than `need` has no such bin: the last bin is reported then, with the count 0.
-__device__ __forceinline__ int find_pivot_bin(CompressShared& sh, int need) {
+template <class SH>
+__device__ __forceinline__ int find_pivot_bin(SH& sh, int need) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     int h[kBinsPer], loc = 0;
 #pragma unroll
@@ -145,8 +151,8 @@ struct KeepRule {
 // first, lower ids first among equal keys.  Every candidate's short key lies in [key_lo, key_hi].
 // Radix select on the key, 11 bits per pass below the highest bit of the range; if the pivot key
 // is shared by more candidates than are still needed, a radix select on the id cuts the tie.
-template <bool BF16>
-__device__ __forceinline__ KeepRule select_exact(CompressShared& sh, int n, int need, uint32_t key_lo, uint32_t key_hi) {
+template <bool BF16, class SH>
+__device__ __forceinline__ KeepRule select_exact(SH& sh, int n, int need, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x;
     uint32_t lo = key_lo;
     const uint32_t range = key_hi - key_lo;
@@ -197,8 +203,8 @@ __device__ __forceinline__ KeepRule select_exact(CompressShared& sh, int n, int 
 // Reduce the n > k candidates to exactly the k that `select_exact` keeps, compacted to the front in
 // any order: survivors already in the first k slots stay, the others fill the slots vacated there.
 // Returns a logit not above the smallest kept one (the new admission threshold).
-template <bool BF16>
-__device__ __forceinline__ float prune_to_k(CompressShared& sh, int n, int k, uint32_t key_lo, uint32_t key_hi) {
+template <bool BF16, class SH>
+__device__ __forceinline__ float prune_to_k(SH& sh, int n, int k, uint32_t key_lo, uint32_t key_hi) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const KeepRule rule = select_exact<BF16>(sh, n, k, key_lo, key_hi);
     uint16_t* holes = reinterpret_cast<uint16_t*>(sh.hist);   // the histogram is free now
@@ -255,7 +261,8 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int P) {
 }
 
 // Clears what order_top_k counts in; a barrier must lie between this and the call.
-__device__ __forceinline__ void order_prepare(CompressShared& sh, int n) {
+template <class SH>
+__device__ __forceinline__ void order_prepare(SH& sh, int n) {
     int t = threadIdx.x;
     asm volatile("" : "+v"(t));                  // (the address is formed here, not held in a register from the top of the kernel)
     for (int i = t; i < kCoarse; i += kT) sh.coarse[i] = 0;
@@ -278,8 +285,9 @@ __device__ __forceinline__ void order_prepare(CompressShared& sh, int n) {
 //     candidates of the bins up to that one are gathered bin by bin, each one's position inside
 //     its bin is the number of larger bin-mates, and the positions below k are kept.
 // A bin too crowded for that sends the row through the radix select and a sorting network.
-template <bool BF16>
-__device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi) {
+template <bool BF16, class SH>
+__device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int V, uint32_t key_lo, uint32_t key_hi) {
+    constexpr int kCap = SH::kCap, kCandPer = kCap / kT, kSortPer = SH::kRecMax / kT;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     uint64_t* buf = reinterpret_cast<uint64_t*>(sh.cand_val);   // cand_val and cand_id, back to back
     const uint32_t kr = key_hi - key_lo;
@@ -406,18 +414,13 @@ __device__ __forceinline__ const uint64_t* order_top_k(CompressShared& sh, int n
     return buf;
 }
 
-// Rank r of tile 0 (m elements of a row of V) whose value is expected to have about
-// k + z*sqrt(k) + z^2 row elements at or above it, z = 4.5; 0 if the optimistic pass does not pay.
-__device__ __forceinline__ int optimistic_rank(int k, int V, int m) {
-    const float r0 = (float)k * (float)m / (float)V;                  // expected rank of the row's k-th value in the tile
-    const float r = r0 + 4.5f * sqrtf(r0) + 20.25f;
-    const float expected = r * (float)V / (float)m;                   // candidates at the end of the row
-    if (expected > 0.8f * (float)kCap) return 0;                      // (r may exceed k: a short record still takes the fast pass)
-    return (int)ceilf(r);
-}
-
 // One row of the compression: the workgroup that runs this writes record `row` of `n_rows`.
-template <bool BF16>
+// SMALL: records of up to kMaxK / 2 entries on rows whose expected candidates fit the smaller buffer (the host
+// decides: launch_compress) - 42 KB of LDS and 80 registers, so that three workgroups share a CU.  This variant
+// holds the optimistic pass only (what the careful pass keeps alive across it costs the registers that the third
+// workgroup needs): a row whose pass fails, or to which it does not apply, gets count = kRetryRow and nothing
+// else, and a second launch of the general kernel, which skips every other row, takes it.
+template <bool BF16, bool SMALL>
 __device__ __forceinline__ void compress_row(
     const int64_t row, const int n_rows,
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
@@ -425,18 +428,20 @@ __device__ __forceinline__ void compress_row(
     float* __restrict__ mass, float* __restrict__ lse,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept, int ahead)
 {
+    using SH = CompressShared<SMALL ? kCapSmall : kCapBig>;
+    constexpr int kCap = SH::kCap, kRecMax = SH::kRecMax, kSortPer = kRecMax / kT;
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    CompressShared& sh = *reinterpret_cast<CompressShared*>(smem_raw);
+    SH& sh = *reinterpret_cast<SH*>(smem_raw);
     // A row is streamed in sub-tiles of SV 16-byte vectors per thread.  The sample from which the first
     // threshold is taken has the size of T0 sub-tiles (8192 elements) and is processed in one piece.
-    using Geom = CompressGeom<BF16>;
+    using Geom = CompressGeom<BF16, SMALL>;
     constexpr int N = Vec<BF16>::N;
     constexpr int SAMPLE = kCompressSample;
     constexpr int SV = Geom::SV, ES = SV * N, SUB = kT * ES;
     constexpr int T0 = SAMPLE / SUB, NV0 = T0 * SV, E0 = NV0 * N;
     constexpr int RING = Geom::RING;             // sub-tile buffers: one in use, the others in flight
     static_assert(Geom::N == N, "vector width");
-    static_assert(SAMPLE <= kCap && T0 >= 1 && T0 < RING && E0 <= 16, "sample geometry");
+    static_assert(T0 >= 1 && T0 < RING && E0 <= 16 && (SMALL || SAMPLE <= kCap), "sample geometry (the careful pass keeps its sample as candidates)");
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: what is indexed by it is addressed from a scalar
     // Row read: the same one, or (downlink record, Section 3.3) the target row of sequence `row` at its
@@ -602,8 +607,8 @@ __device__ __forceinline__ void compress_row(
     // that they stay straight-line code (predication by EXEC, no branches for the compiler to lay
     // out): claim_asm forms the lane mask, claims under it and hands the mask on; put_asm waits for
     // the claimed slots and writes under the same masks.  The counter
-    // counts bytes of cand_val (4 per candidate) so that a masked slot is the LDS address; slots wrap
-    // around the buffer: once the count has passed its end the pass is lost anyway.
+    // counts bytes of cand_val (4 per candidate) so that a clamped slot is the LDS address; slots behind
+    // the buffer's end fall onto its last one: once the count has passed the end the pass is lost anyway.
     typedef __attribute__((address_space(3))) unsigned lds_u32;
     const unsigned cnt_addr = (unsigned)(uintptr_t)(lds_u32*)&sh.cnt;
     const unsigned val_addr = (unsigned)(uintptr_t)(lds_u32*)&sh.cand_val[0];
@@ -627,7 +632,7 @@ __device__ __forceinline__ void compress_row(
     };
     auto put_asm = [&, wrap](auto nvv_tag, const float* v, int* slot, const unsigned long long* passed, int x0) {
         constexpr int NVV = decltype(nvv_tag)::value;
-        static_assert(NVV == 2 || NVV == 4, "the wait names every slot");
+        static_assert(NVV * N == 8 || NVV * N == 16, "the wait names every slot");
         // the claimed slots have arrived (the running sum is named so that the statistics stay in front)
         if constexpr (NVV * N == 8)
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]), "+v"(slot[3]),
@@ -648,34 +653,35 @@ __device__ __forceinline__ void compress_row(
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int i = i0 + u;
-                at[u] = ((unsigned)slot[i] & wrap) + va;
+                                at[u] = min((unsigned)slot[i], wrap) + va;
                 id[u] = (unsigned)(x0 + (i / N) * kT * N + i % N);
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 unsigned long long saved;
                 asm volatile("s_and_saveexec_b64 %[sv], %[m]\n\t"
-                             "ds_write2st64_b32 %[at], %[x], %[id] offset1:128\n\t"
+                             "ds_write2st64_b32 %[at], %[x], %[id] offset1:%c[o1]\n\t"
                              "s_mov_b64 exec, %[sv]"
                              : [sv] "=&s"(saved)
-                             : [m] "s"(passed[i0 + u]), [at] "v"(at[u]), [id] "v"(id[u]), [x] "v"(v[i0 + u])
+                             : [m] "s"(passed[i0 + u]), [at] "v"(at[u]), [id] "v"(id[u]), [x] "v"(v[i0 + u]), [o1] "n"(kCap / 64)
                              : "memory", "scc");
             }
         }
     };
-    static_assert(offsetof(CompressShared, cand_id) - offsetof(CompressShared, cand_val) == 128 * 64 * 4,
-                  "ds_write2st64 offset1:128 reaches cand_id from cand_val");
+    static_assert(offsetof(SH, cand_id) - offsetof(SH, cand_val) == (kCap / 64) * 64 * 4,
+                  "ds_write2st64 offset1 reaches cand_id from cand_val");
 
     const bool more = n_sub > T0;                // the row goes on behind the sample
-    const int r_opt = more ? optimistic_rank(k, V, SAMPLE) : 0;
+    const int r_opt = more ? optimistic_rank(k, V, SAMPLE, kCap) : 0;
     float M = kNegInf;
     double S = 0.0;
     uint32_t key_lo = 0, key_hi = 0;
     int n_held = -1;                             // candidates held at the end of the row (-1: read the counter)
     bool fill = false;                           // fewer entries above -inf than k: masked entries fill the record up
 
-    for (int attempt = r_opt > 0 ? 0 : 1; attempt < 2; ++attempt) {
-        const bool optimistic = attempt == 0;
+    bool row_done = false;
+    for (int attempt = r_opt > 0 ? 0 : 1; attempt < (SMALL ? 1 : 2); ++attempt) {
+        const bool optimistic = SMALL || attempt == 0;
         if (tid == 0) {
             sh.cnt = 0;
             sh.overflowed = 0;
@@ -952,7 +958,12 @@ __device__ __forceinline__ void compress_row(
             }
         }
         key_hi = short_key<BF16>(__float_as_uint(M));
+        row_done = true;
         break;
+    }
+    if (SMALL && !row_done) {                    // (uniform: the verdict was read from LDS behind a barrier)
+        if (tid == 0) count[row] = kRetryRow;
+        return;
     }
 
     // ---- While this row is ordered and emitted, the first sub-tiles of the row that will take a slot like
@@ -979,9 +990,9 @@ __device__ __forceinline__ void compress_row(
 
     // A mostly masked row with fewer entries above -inf than k (all of them are held): the record goes on with
     // masked entries (probability 0), lowest ids first, i.e. with the lowest ids that are not held.  There are
-    // k - n of them among the ids below n + (k - n) <= 2 * kMaxK: a bitmap of the held ids in that range and the
+    // k - n of them among the ids below n + (k - n) <= 2 * kRecMax: a bitmap of the held ids in that range and the
     // number of free ids in front of each of its words locate the j-th.
-    constexpr int kFillWords = 2 * kMaxK / 32;
+    constexpr int kFillWords = 2 * kRecMax / 32;
     static_assert(kFillWords <= kT && 2 * kFillWords <= kBins, "the bitmap and its prefix live in the histogram");
     uint32_t* const held_bits = sh.hist;
     uint32_t* const free_before = sh.hist + kFillWords;
@@ -992,7 +1003,7 @@ __device__ __forceinline__ void compress_row(
         __syncthreads();
         for (int i = t; i < n; i += kT) {
             const uint32_t id = kIdMask - ((uint32_t)sorted[i] & kIdMask);
-            if (id < 2u * kMaxK) atomicOr(&held_bits[id >> 5], 1u << (id & 31u));
+            if (id < 2u * kRecMax) atomicOr(&held_bits[id >> 5], 1u << (id & 31u));
         }
         __syncthreads();
         const int z = t < kFillWords ? 32 - __popc(held_bits[t]) : 0;
@@ -1116,15 +1127,46 @@ __device__ __forceinline__ void compress_row(
     }
 }
 
-template <bool BF16>
-__global__ __launch_bounds__(kT, kT / 128) void compress_kernel(
+template <bool BF16, bool SMALL>
+__global__ __launch_bounds__(kT, SMALL ? 6 : 4) void compress_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
     float* __restrict__ mass, float* __restrict__ lse,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept, int ahead)
 {
-    compress_row<BF16>(blockIdx.x, (int)gridDim.x, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
-                       seq_off, n_accept, ahead);
+    compress_row<BF16, SMALL>(blockIdx.x, (int)gridDim.x, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+                              seq_off, n_accept, ahead);
+}
+
+// The rows that the small variant marked with count = kRetryRow, through the general code: a few workgroups, each
+// looking through its share of the counts (one row per thread and step) and compressing the rows it finds marked.
+// (Launching one general workgroup per row just to look would cost tens of microseconds: its LDS makes the launch slow.)
+template <bool BF16>
+__global__ __launch_bounds__(kT, 4) void compress_retry_kernel(
+    const void* __restrict__ logits, int64_t ld, int n_rows, int V, float inv_T, int k, float top_p,
+    int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
+    float* __restrict__ mass, float* __restrict__ lse,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept)
+{
+    __shared__ int marked[kT];
+    __shared__ int n_marked;
+    const int per = (n_rows + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int first = (int)blockIdx.x * per, last = min(first + per, n_rows);
+    for (int r0 = first; r0 < last; r0 += kT) {
+        if (threadIdx.x == 0) n_marked = 0;
+        __syncthreads();
+        const int r = r0 + (int)threadIdx.x;
+        if (r < last && count[r] == kRetryRow) marked[atomicAdd(&n_marked, 1)] = r;
+        __syncthreads();
+        const int n = n_marked;
+        for (int i = 0; i < n; ++i) {
+            const int row = marked[i];
+            compress_row<BF16, false>(row, n_rows, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+                                      seq_off, n_accept, 0);
+            __syncthreads();                     // (the row's last reads of LDS are done before the next one resets it)
+        }
+        __syncthreads();
+    }
 }
 
 // Both streams of a small round in one launch (the draft rows' compression and the target rows' statistics do
@@ -1139,8 +1181,8 @@ __global__ __launch_bounds__(kT, 2) void round_stream_kernel(
     float* __restrict__ tgt_max, float* __restrict__ tgt_sum, float* __restrict__ tgt_lse)
 {
     if ((int)blockIdx.x < n_draft) {
-        compress_row<BF16>(blockIdx.x, n_draft, draft_logits, ld_d, V, inv_T, k, top_p, idx, prob, count, mass, lse,
-                           nullptr, nullptr, 0);
+        compress_row<BF16, false>(blockIdx.x, n_draft, draft_logits, ld_d, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+                                  nullptr, nullptr, 0);
     } else {
         row_stats_row<BF16, 2, kT>((int64_t)blockIdx.x - n_draft, tgt_logits, ld_t, V, inv_T, tgt_max, tgt_sum, tgt_lse);
     }
@@ -1261,35 +1303,59 @@ __global__ __launch_bounds__(256) void sample_draft_vec_kernel(
 
 }  // namespace
 
+// The small variant (three workgroups per CU) serves records of up to kMaxK / 2 entries on rows long enough that the
+// optimistic pass applies and its expected candidates fit the smaller buffer with room to spare (the kernel evaluates
+// the same function with the full allowance, so it agrees), when there are more rows than the general kernel holds
+// at a time (else the third workgroup per CU has nothing to do).  A second launch, of the general kernel, takes the
+// rows the small variant gave up (none, as a rule: its workgroups then leave at once).
+static bool small_variant_serves(int k, int V, int n_rows, int cus)
+{
+    return k <= CompressShared<kCapSmall>::kRecMax && V >= 4 * kCompressSample && n_rows > 2 * cus &&
+           optimistic_rank(k, V, kCompressSample, kCapSmall, 4.5f) > 0;
+}
+
 hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
                            float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream)
 {
-    static DeviceFlags limit_raised[2] = {};
-    static std::atomic<int> resident[kMaxDevices] = {};   // rows resident at a time (2 workgroups per CU): the distance of the look-ahead loads
-    const size_t smem = sizeof(CompressShared);
-    auto f32 = compress_kernel<false>;
-    auto b16 = compress_kernel<true>;
-    const int which = dtype == 1;
+    static DeviceFlags limit_raised[6] = {};
+    static std::atomic<int> cu_count[kMaxDevices] = {};
+    const int bf = dtype == 1 ? 1 : 0;
+    const void* const kernels[6] = {(const void*)compress_kernel<false, false>, (const void*)compress_kernel<true, false>,
+                                    (const void*)compress_kernel<false, true>, (const void*)compress_kernel<true, true>,
+                                    (const void*)compress_retry_kernel<false>, (const void*)compress_retry_kernel<true>};
+    const size_t smem_big = sizeof(CompressShared<kCapBig>), smem_small = sizeof(CompressShared<kCapSmall>);
     int dev = 0;
-    {
-        hipError_t e = raise_lds_limit_once(which ? (const void*)b16 : (const void*)f32, smem, limit_raised[which], dev);
+    {   // (every variant of the dtype: which of them a call takes depends on its sizes)
+        hipError_t e = raise_lds_limit_once(kernels[bf], smem_big, limit_raised[bf], dev);
+        if (e == hipSuccess) e = raise_lds_limit_once(kernels[2 + bf], smem_small, limit_raised[2 + bf], dev);
+        if (e == hipSuccess) e = raise_lds_limit_once(kernels[4 + bf], smem_big, limit_raised[4 + bf], dev);
         if (e != hipSuccess) return e;
     }
     if (n_rows == 0) return hipSuccess;
-    int ahead = 0;
-    if (!seq_off) {                              // (no look-ahead with a row map: the next row is not known from the row number)
-        int res = resident[dev].load(std::memory_order_relaxed);
-        if (res == 0) {                          // (first use on this device; a second thread here computes the same value)
-            int cus = 0;
-            res = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? 2 * cus : -1;
-            resident[dev].store(res, std::memory_order_relaxed);
-        }
-        ahead = res > 0 ? res : 0;
+    int cus = cu_count[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {                              // (first use on this device; a second thread here computes the same value)
+        cus = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? cus : -1;
+        cu_count[dev].store(cus, std::memory_order_relaxed);
     }
+    const bool small = cus > 0 && small_variant_serves(k, V, n_rows, cus);
+    // rows resident at a time (2 workgroups per CU, 3 of the small variant): the distance of the look-ahead loads
+    // (no look-ahead with a row map: the next row is not known from the row number)
+    const int ahead = (!seq_off && cus > 0) ? (small ? 3 : 2) * cus : 0;
     const float inv_T = 1.0f / temperature;
-    if (which) hipLaunchKernelGGL(b16, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
-    else       hipLaunchKernelGGL(f32, dim3(n_rows), dim3(kT), smem, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead);
+#define PICOSPEC_COMPRESS(BF, SM, SMEM) \
+    hipLaunchKernelGGL((compress_kernel<BF, SM>), dim3(n_rows), dim3(kT), SMEM, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead)
+#define PICOSPEC_RETRY(BF) \
+    hipLaunchKernelGGL((compress_retry_kernel<BF>), dim3(min(64, (n_rows + kT - 1) / kT)), dim3(kT), smem_big, stream, logits, ld, n_rows, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept)
+    if (small) {
+        if (bf) PICOSPEC_COMPRESS(true, true, smem_small); else PICOSPEC_COMPRESS(false, true, smem_small);
+        if (hipError_t e = hipGetLastError()) return e;
+        if (bf) PICOSPEC_RETRY(true); else PICOSPEC_RETRY(false);
+    } else {
+        if (bf) PICOSPEC_COMPRESS(true, false, smem_big); else PICOSPEC_COMPRESS(false, false, smem_big);
+    }
+#undef PICOSPEC_RETRY
+#undef PICOSPEC_COMPRESS
     return hipGetLastError();
 }
 
@@ -1299,7 +1365,7 @@ hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d
                                float* tgt_max, float* tgt_sum, float* tgt_lse, hipStream_t stream)
 {
     static DeviceFlags limit_raised[2] = {};
-    const size_t smem = sizeof(CompressShared);
+    const size_t smem = sizeof(CompressShared<kCapBig>);
     auto f32 = round_stream_kernel<false>;
     auto b16 = round_stream_kernel<true>;
     const int which = dtype == 1;

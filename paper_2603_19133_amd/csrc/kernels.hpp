@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <cmath>
 
 namespace picospec {
 
@@ -14,6 +15,27 @@ constexpr int kMaxV = 1 << 20;
 // picospec_round: draft + target rows up to which the two-launch schedule is used (the chip holds 512 compress
 // workgroups at a time; beyond that the separate kernels, each with its own launch shape, are as fast or faster)
 constexpr int kRoundSmallRows = 512;
+
+// The optimistic pass of the compress kernel takes its threshold from a sample of m elements of a row of V: the value
+// of rank r in the sample, and every row element at or above it becomes a candidate.  With f = m / V the sample holds
+// X ~ Binomial(k, f) of the row's k largest; the pass finds fewer than k candidates iff X >= r, so
+//     r = k f + z sqrt(k f (1 - f)) + z^2 / 3      (mean + z standard deviations + the term that covers small means)
+// with z = 4.5 (or 4, see below).  It overflows a buffer of `cap` slots iff the sample holds fewer than r of the row's
+// `cap` largest, Binomial(cap, f): r must stay z_over standard deviations below cap f.  A pass that fails either way is
+// repeated the careful way, so the margins only trade a rare slow row against the candidates every row carries.
+// 0: no rank satisfies both (the careful pass takes the row).  The host evaluates the same function, with a slightly
+// larger z_over, to choose the kernel variant.
+__host__ __device__ inline int optimistic_rank(int k, int V, int m, int cap, float z_over = 4.45f) {
+    const float f = (float)m / (float)V;
+    const float lam = (float)k * f, lam_cap = (float)cap * f;
+    const float sd_cap = sqrtf(lam_cap * (1.f - f));
+    const float zs[2] = {4.5f, 4.0f};
+    for (int i = 0; i < 2; ++i) {
+        const float r = ceilf(lam + zs[i] * sqrtf(lam * (1.f - f)) + zs[i] * zs[i] * (1.f / 3.f));
+        if (lam_cap - r >= z_over * sd_cap) return (int)r;           // (r may exceed k: a short record still takes the fast pass)
+    }
+    return 0;
+}
 
 // Kernels whose dynamic LDS exceeds the 64 KB default need their limit raised once per device and kernel.
 // `done` is the caller's per-device record for that kernel; the current device's ordinal comes back in `dev`.

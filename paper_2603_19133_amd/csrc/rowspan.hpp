@@ -25,6 +25,9 @@ namespace picospec {
 #ifndef PICOSPEC_COMPRESS_RING
 #define PICOSPEC_COMPRESS_RING 4
 #endif
+#ifndef PICOSPEC_SMALL_BF16_RING
+#define PICOSPEC_SMALL_BF16_RING 5
+#endif
 
 constexpr int kCompressThreads = PICOSPEC_COMPRESS_THREADS;   // one workgroup per row
 constexpr int kCompressSample = 8192;                         // elements of the sample that places the threshold
@@ -37,12 +40,14 @@ __host__ __device__ inline int64_t buffer_lane_read_end(int64_t size, int64_t sc
     return scalar_off + lane_off + 16 <= size ? scalar_off + lane_off + 16 : 0;
 }
 
-template <bool BF16>
+// SMALL: the variant for short records (three workgroups per CU: fewer registers, a sub-tile of 8 elements per thread)
+template <bool BF16, bool SMALL>
 struct CompressGeom {
     static constexpr int N = BF16 ? 8 : 4;                                                   // elements per vector
-    static constexpr int SV = (2 * kCompressThreads * N <= kCompressSample) ? 2 : 1;         // vectors per thread and sub-tile
+    static constexpr int SV = (BF16 && SMALL) ? 1 : 2;                                       // vectors per thread and sub-tile
     static constexpr int SUB_VECS = kCompressThreads * SV;                                   // vectors per sub-tile
-    static constexpr int RING = PICOSPEC_COMPRESS_RING * (2 / SV);                           // sub-tile buffers (look-ahead depth)
+    static constexpr int RING = (BF16 && SMALL) ? PICOSPEC_SMALL_BF16_RING : PICOSPEC_COMPRESS_RING * (2 / SV);            // sub-tile buffers (look-ahead depth)
+    static_assert(kCompressSample % (SUB_VECS * N) == 0, "the sample is a whole number of sub-tiles");
     // first vector of group j (one vector per thread: thread tid takes vector tid of the group) of sub-tile `sub`
     __host__ __device__ static int group_first(int sub, int j) { return sub * SUB_VECS + j * kCompressThreads; }
 };

@@ -78,36 +78,39 @@ def test_compress_sizes_and_tails(gpu, pu, ps, V, k, dtype):
                                      "two_values", "sawtooth", "trend_down", "trend_up", "head_hot", "head_cold",
                                      "hot_cluster", "period_of_the_sample", "masked_3pct", "masked_block", "masked_few",
                                      "masked_half"])
+# (three rows: the general kernel at two record lengths; 600 rows of a short record on long rows: the variant with three
+#  workgroups per CU, which leaves the rows its optimistic pass cannot take to a second launch of the general kernel)
+@pytest.mark.parametrize("R,k", [(3, 777), (3, 2500), (600, 777)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
-    _announce("compress adversarial", pattern, dtype)
-    V, k = 40000, 777
+def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype, R, k):
+    _announce("compress adversarial", pattern, dtype, R, k)
+    V = 40000
     rng = np.random.default_rng(5)
     if pattern == "ties":
-        z = rng.integers(-6, 7, (3, V)).astype(np.float32)
+        z = rng.integers(-6, 7, (R, V)).astype(np.float32)
     elif pattern == "all_equal":
-        z = np.full((3, V), 1.5, np.float32)
+        z = np.full((R, V), 1.5, np.float32)
     elif pattern == "ascending":        # defeats the running threshold: every element is admitted
-        z = np.tile(np.linspace(-8, 8, V, dtype=np.float32), (3, 1))
+        z = np.tile(np.linspace(-8, 8, V, dtype=np.float32), (R, 1))
     elif pattern == "descending":
-        z = np.tile(np.linspace(8, -8, V, dtype=np.float32), (3, 1))
+        z = np.tile(np.linspace(8, -8, V, dtype=np.float32), (R, 1))
     elif pattern == "neg_inf":
-        z = np.where(rng.random((3, V)) < 0.99, -np.inf, rng.standard_normal((3, V))).astype(np.float32)
+        z = np.where(rng.random((R, V)) < 0.99, -np.inf, rng.standard_normal((R, V))).astype(np.float32)
     elif pattern == "signed_zero":
-        z = np.where(rng.random((3, V)) < 0.5, -0.0, 0.0).astype(np.float32)
+        z = np.where(rng.random((R, V)) < 0.5, -0.0, 0.0).astype(np.float32)
         z[:, ::97] = -1.0
     elif pattern == "two_values":
-        z = np.where(rng.random((3, V)) < 0.01, 2.0, -2.0).astype(np.float32)
+        z = np.where(rng.random((R, V)) < 0.01, 2.0, -2.0).astype(np.float32)
     elif pattern == "sawtooth":
-        z = np.tile((np.arange(V) % 1000).astype(np.float32) * 0.01, (3, 1))
+        z = np.tile((np.arange(V) % 1000).astype(np.float32) * 0.01, (R, 1))
     elif pattern.startswith("masked"):
         # vocabulary masks (-inf everywhere but on the allowed ids): more allowed ids than k, fewer than k (the record
         # is then filled up with masked ids in ascending order), a block of ids, half of the vocabulary
-        z = (rng.standard_normal((3, V)) * 3).astype(np.float32)
+        z = (rng.standard_normal((R, V)) * 3).astype(np.float32)
         ids = np.arange(V)
-        allowed = {"masked_3pct": rng.random((3, V)) < 0.03, "masked_few": rng.random((3, V)) < 0.002,
-                   "masked_block": np.tile((ids >= 20000) & (ids < 21500), (3, 1)),
-                   "masked_half": rng.random((3, V)) < 0.5}[pattern]
+        allowed = {"masked_3pct": rng.random((R, V)) < 0.03, "masked_few": rng.random((R, V)) < 0.002,
+                   "masked_block": np.tile((ids >= 20000) & (ids < 21500), (R, 1)),
+                   "masked_half": rng.random((R, V)) < 0.5}[pattern]
         z = np.where(allowed, z, -np.inf).astype(np.float32)
     else:
         # values that depend on the vocabulary id, as logits do (frequent tokens sit at low ids): the threshold
@@ -117,11 +120,12 @@ def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype):
                 "head_hot": np.where(ids < 8192, 6.0, 0.0), "head_cold": np.where(ids < 8192, -6.0, 0.0),
                 "hot_cluster": np.where((ids > 20000) & (ids < 20600), 9.0, 0.0),       # between the sample's runs or on them
                 "period_of_the_sample": 4.0 * np.cos(2 * np.pi * ids * 256 / V)}[pattern]
-        z = (rng.standard_normal((3, V)) * 3 + bias).astype(np.float32)
+        z = (rng.standard_normal((R, V)) * 3 + bias).astype(np.float32)
     _compress_case(pu, ps, gpu, z, V, 1.3, k, dtype=dtype)
 
 
-@pytest.mark.parametrize("V,k,scale", [(10108, 1400, 0.5), (10108, 1700, 0.5), (12300, 2000, 0.5), (16500, 3000, 0.5)])
+@pytest.mark.parametrize("V,k,scale", [(10108, 1400, 0.5), (10108, 1700, 0.5), (12300, 2000, 0.5), (16500, 3000, 0.5),
+                                       (36000, 1400, 0.5), (40108, 2000, 0.5), (33000, 700, 0.5)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_compress_ties_at_the_cut_when_the_buffer_fills_in_mid_sub_tile(gpu, pu, ps, V, k, scale, dtype):
     """Rows of a few distinct values whose k-th largest is shared by hundreds of entries, of a length at which
@@ -134,11 +138,12 @@ def test_compress_ties_at_the_cut_when_the_buffer_fills_in_mid_sub_tile(gpu, pu,
 
 
 @pytest.mark.parametrize("shift", [1, 2, 3, 5])
+@pytest.mark.parametrize("V", [20001, 50001])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_compress_unaligned_rows(gpu, pu, ps, shift, dtype):
+def test_compress_unaligned_rows(gpu, pu, ps, shift, dtype, V):
     """Row starts that are not 16-byte aligned (odd leading dimension, offset base pointer)."""
-    _announce("compress unaligned", shift, dtype)
-    V, ld, k = 20001, 20001 + shift, 300
+    _announce("compress unaligned", shift, dtype, V)
+    ld, k = V + shift, 300
     rng = np.random.default_rng(shift)
     full = (rng.standard_normal((4, ld)) * 2).astype(np.float32)
     stored = full if dtype == "f32" else W.to_bf16_bits(full)
@@ -161,6 +166,13 @@ def test_compress_every_pass_with_the_chip_full(gpu, pu, ps, pattern, dtype):
     its other passes: values that trend with the id, masks that leave more or fewer ids than k, rows of a few
     distinct values whose buffer fills, and all of them mixed row by row."""
     _chip_full_case(gpu, pu, ps, pattern, dtype, 1100, 12300, 600)
+
+
+@pytest.mark.parametrize("pattern", ["trend", "masked_above_k", "masked_below_k", "few_values", "mixed"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_every_pass_with_the_chip_full_short_records(gpu, pu, ps, pattern, dtype):
+    """The same through the kernel's variant for short records on long rows (three workgroups per CU)."""
+    _chip_full_case(gpu, pu, ps, pattern, dtype, 1100, 40000, 600)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -193,13 +205,14 @@ def _chip_full_case(gpu, pu, ps, pattern, dtype, rows, V, k):
     _compress_case(pu, ps, gpu, z.astype(np.float32), V, 1.0, k, dtype=dtype)
 
 
+@pytest.mark.parametrize("shape", [(1237, 9001, 9003, 70), (1741, 33001, 33003, 70)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_compress_more_rows_than_resident_workgroups(gpu, pu, ps, dtype):
+def test_compress_more_rows_than_resident_workgroups(gpu, pu, ps, dtype, shape):
     """More rows than the chip holds at a time (the look-ahead loads of the next generation of rows are
     live), odd leading dimension so that most rows start off a 16-byte boundary, and a row count that is
     not a multiple of anything; also the same through the row statistics."""
-    _announce("compress many rows", dtype)
-    rows, V, ld, k = 1237, 9001, 9003, 70
+    _announce("compress many rows", dtype, shape)
+    rows, V, ld, k = shape
     rng = np.random.default_rng(12)
     full = (rng.standard_normal((rows, ld)) * 3).astype(np.float32)
     stored = full if dtype == "f32" else W.to_bf16_bits(full)
