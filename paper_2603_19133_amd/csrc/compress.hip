@@ -420,7 +420,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
 // holds the optimistic pass only (what the careful pass keeps alive across it costs the registers that the third
 // workgroup needs): a row whose pass fails, or to which it does not apply, gets count = kRetryRow and nothing
 // else, and a second launch of the general kernel, which skips every other row, takes it.
-template <bool BF16, bool SMALL>
+template <bool BF16, bool SMALL, bool FAST = SMALL>
 __device__ __forceinline__ void compress_row(
     const int64_t row, const int n_rows,
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
@@ -441,7 +441,7 @@ __device__ __forceinline__ void compress_row(
     constexpr int T0 = SAMPLE / SUB, NV0 = T0 * SV, E0 = NV0 * N;
     constexpr int RING = Geom::RING;             // sub-tile buffers: one in use, the others in flight
     static_assert(Geom::N == N, "vector width");
-    static_assert(T0 >= 1 && T0 < RING && E0 <= 16 && (SMALL || SAMPLE <= kCap), "sample geometry (the careful pass keeps its sample as candidates)");
+    static_assert(T0 >= 1 && T0 < RING && E0 <= 16 && (FAST || SAMPLE <= kCap), "sample geometry (the careful pass keeps its sample as candidates)");
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: what is indexed by it is addressed from a scalar
     // Row read: the same one, or (downlink record, Section 3.3) the target row of sequence `row` at its
@@ -680,8 +680,9 @@ __device__ __forceinline__ void compress_row(
     bool fill = false;                           // fewer entries above -inf than k: masked entries fill the record up
 
     bool row_done = false;
-    for (int attempt = r_opt > 0 ? 0 : 1; attempt < (SMALL ? 1 : 2); ++attempt) {
-        const bool optimistic = SMALL || attempt == 0;
+    static_assert(FAST || !SMALL, "the small buffer cannot hold the careful pass's sample");
+    for (int attempt = r_opt > 0 ? 0 : 1; attempt < (FAST ? 1 : 2); ++attempt) {
+        const bool optimistic = FAST || attempt == 0;
         if (tid == 0) {
             sh.cnt = 0;
             sh.overflowed = 0;
@@ -961,7 +962,7 @@ __device__ __forceinline__ void compress_row(
         row_done = true;
         break;
     }
-    if (SMALL && !row_done) {                    // (uniform: the verdict was read from LDS behind a barrier)
+    if (FAST && !row_done) {                     // (uniform: the verdict was read from LDS behind a barrier)
         if (tid == 0) count[row] = kRetryRow;
         return;
     }
@@ -1127,15 +1128,15 @@ __device__ __forceinline__ void compress_row(
     }
 }
 
-template <bool BF16, bool SMALL>
+template <bool BF16, bool SMALL, bool FAST>
 __global__ __launch_bounds__(kT, SMALL ? 6 : 4) void compress_kernel(
     const void* __restrict__ logits, int64_t ld, int V, float inv_T, int k, float top_p,
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
     float* __restrict__ mass, float* __restrict__ lse,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept, int ahead)
 {
-    compress_row<BF16, SMALL>(blockIdx.x, (int)gridDim.x, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
-                              seq_off, n_accept, ahead);
+    compress_row<BF16, SMALL, FAST>(blockIdx.x, (int)gridDim.x, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+                                    seq_off, n_accept, ahead);
 }
 
 // The rows that the small variant marked with count = kRetryRow, through the general code: a few workgroups, each
@@ -1161,7 +1162,7 @@ __global__ __launch_bounds__(kT, 4) void compress_retry_kernel(
         const int n = n_marked;
         for (int i = 0; i < n; ++i) {
             const int row = marked[i];
-            compress_row<BF16, false>(row, n_rows, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+            compress_row<BF16, false, false>(row, n_rows, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse,
                                       seq_off, n_accept, 0);
             __syncthreads();                     // (the row's last reads of LDS are done before the next one resets it)
         }
@@ -1181,7 +1182,7 @@ __global__ __launch_bounds__(kT, 2) void round_stream_kernel(
     float* __restrict__ tgt_max, float* __restrict__ tgt_sum, float* __restrict__ tgt_lse)
 {
     if ((int)blockIdx.x < n_draft) {
-        compress_row<BF16, false>(blockIdx.x, n_draft, draft_logits, ld_d, V, inv_T, k, top_p, idx, prob, count, mass, lse,
+        compress_row<BF16, false, false>(blockIdx.x, n_draft, draft_logits, ld_d, V, inv_T, k, top_p, idx, prob, count, mass, lse,
                                   nullptr, nullptr, 0);
     } else {
         row_stats_row<BF16, 2, kT>((int64_t)blockIdx.x - n_draft, tgt_logits, ld_t, V, inv_T, tgt_max, tgt_sum, tgt_lse);
@@ -1305,12 +1306,10 @@ __global__ __launch_bounds__(256) void sample_draft_vec_kernel(
 
 // The small variant (three workgroups per CU) serves records of up to kMaxK / 2 entries on rows long enough that the
 // optimistic pass applies and its expected candidates fit the smaller buffer with room to spare (the kernel evaluates
-// the same function with the full allowance, so it agrees), when there are more rows than the general kernel holds
-// at a time (else the third workgroup per CU has nothing to do).  A second launch, of the general kernel, takes the
-// rows the small variant gave up (none, as a rule: its workgroups then leave at once).
-static bool small_variant_serves(int k, int V, int n_rows, int cus)
+// the same function with a slightly smaller allowance, so it agrees).
+static bool small_variant_serves(int k, int V)
 {
-    return k <= CompressShared<kCapSmall>::kRecMax && V >= 4 * kCompressSample && n_rows > 2 * cus &&
+    return k <= CompressShared<kCapSmall>::kRecMax && V >= 4 * kCompressSample &&
            optimistic_rank(k, V, kCompressSample, kCapSmall, 4.5f) > 0;
 }
 
@@ -1318,18 +1317,21 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
                            int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass,
                            float* lse, const int32_t* seq_off, const int32_t* n_accept, hipStream_t stream)
 {
-    static DeviceFlags limit_raised[6] = {};
+    static DeviceFlags limit_raised[8] = {};
     static std::atomic<int> cu_count[kMaxDevices] = {};
     const int bf = dtype == 1 ? 1 : 0;
-    const void* const kernels[6] = {(const void*)compress_kernel<false, false>, (const void*)compress_kernel<true, false>,
-                                    (const void*)compress_kernel<false, true>, (const void*)compress_kernel<true, true>,
+    // general (both passes in one kernel) / fast (optimistic pass only, rows it gives up marked for the retry kernel),
+    // the latter with the large or the small candidate buffer
+    const void* const kernels[8] = {(const void*)compress_kernel<false, false, false>, (const void*)compress_kernel<true, false, false>,
+                                    (const void*)compress_kernel<false, false, true>, (const void*)compress_kernel<true, false, true>,
+                                    (const void*)compress_kernel<false, true, true>, (const void*)compress_kernel<true, true, true>,
                                     (const void*)compress_retry_kernel<false>, (const void*)compress_retry_kernel<true>};
     const size_t smem_big = sizeof(CompressShared<kCapBig>), smem_small = sizeof(CompressShared<kCapSmall>);
     int dev = 0;
     {   // (every variant of the dtype: which of them a call takes depends on its sizes)
-        hipError_t e = raise_lds_limit_once(kernels[bf], smem_big, limit_raised[bf], dev);
-        if (e == hipSuccess) e = raise_lds_limit_once(kernels[2 + bf], smem_small, limit_raised[2 + bf], dev);
-        if (e == hipSuccess) e = raise_lds_limit_once(kernels[4 + bf], smem_big, limit_raised[4 + bf], dev);
+        hipError_t e = hipSuccess;
+        for (int v = 0; v < 4 && e == hipSuccess; ++v)
+            e = raise_lds_limit_once(kernels[2 * v + bf], v == 2 ? smem_small : smem_big, limit_raised[2 * v + bf], dev);
         if (e != hipSuccess) return e;
     }
     if (n_rows == 0) return hipSuccess;
@@ -1338,21 +1340,28 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
         cus = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 ? cus : -1;
         cu_count[dev].store(cus, std::memory_order_relaxed);
     }
-    const bool small = cus > 0 && small_variant_serves(k, V, n_rows, cus);
+    // Calls of more rows than the chip holds at a time take the fast kernels (fewer registers: the careful pass is
+    // not in them) and pay one small launch more; smaller calls are bound by that launch and take the general kernel.
+    const bool fast = cus > 0 && n_rows > 2 * cus && V > kCompressSample;
+    const bool small = fast && small_variant_serves(k, V);
     // rows resident at a time (2 workgroups per CU, 3 of the small variant): the distance of the look-ahead loads
     // (no look-ahead with a row map: the next row is not known from the row number)
     const int ahead = (!seq_off && cus > 0) ? (small ? 3 : 2) * cus : 0;
     const float inv_T = 1.0f / temperature;
-#define PICOSPEC_COMPRESS(BF, SM, SMEM) \
-    hipLaunchKernelGGL((compress_kernel<BF, SM>), dim3(n_rows), dim3(kT), SMEM, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead)
+#define PICOSPEC_COMPRESS(BF, SM, FA, SMEM) \
+    hipLaunchKernelGGL((compress_kernel<BF, SM, FA>), dim3(n_rows), dim3(kT), SMEM, stream, logits, ld, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept, ahead)
 #define PICOSPEC_RETRY(BF) \
     hipLaunchKernelGGL((compress_retry_kernel<BF>), dim3(min(64, (n_rows + kT - 1) / kT)), dim3(kT), smem_big, stream, logits, ld, n_rows, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept)
     if (small) {
-        if (bf) PICOSPEC_COMPRESS(true, true, smem_small); else PICOSPEC_COMPRESS(false, true, smem_small);
+        if (bf) PICOSPEC_COMPRESS(true, true, true, smem_small); else PICOSPEC_COMPRESS(false, true, true, smem_small);
+    } else if (fast) {
+        if (bf) PICOSPEC_COMPRESS(true, false, true, smem_big); else PICOSPEC_COMPRESS(false, false, true, smem_big);
+    } else {
+        if (bf) PICOSPEC_COMPRESS(true, false, false, smem_big); else PICOSPEC_COMPRESS(false, false, false, smem_big);
+    }
+    if (fast) {
         if (hipError_t e = hipGetLastError()) return e;
         if (bf) PICOSPEC_RETRY(true); else PICOSPEC_RETRY(false);
-    } else {
-        if (bf) PICOSPEC_COMPRESS(true, false, smem_big); else PICOSPEC_COMPRESS(false, false, smem_big);
     }
 #undef PICOSPEC_RETRY
 #undef PICOSPEC_COMPRESS
