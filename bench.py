@@ -9,6 +9,11 @@ positions per second, the HBM roofline of the dominant kernel (the compress pass
 timed on a bounded sample of the same workload on this machine's host cores.  The timed steps carry one pair
 of HIP events each, around the compress call (the kernel the roofline is quoted for); the per-call figures
 in `call_ms` come from a few extra steps after the timed region.
+
+The timed rounds are consecutive and every one has uniforms of its own, prepared on the device beforehand.  The
+smaller configurations cycle through several resident input sets so that no round finds its logits in the caches;
+cfg5 (ragged asynchronous rounds) runs its 100 consecutive rounds over eight resident rounds of the workload (rounds
+0..7, each with its own draft lengths and row packing: all 100 would need 280 GB of logits).
 """
 from __future__ import annotations
 
@@ -23,9 +28,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
-# HBM traffic of one compress launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# the same counters' reading for a plain copy kernel of known size; see profiles/.  Bytes per launch.
-MEASURED_TRAFFIC = {"cfg4": 2.672e9, "cfg5": 1.387e9, "cfg3": 1.364e8}   # profiles/*.md
+# HBM traffic of one compress launch (bytes), a constant taken from the rocprofv3 --pmc runs summarised under
+# profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters' reading for a plain copy of known size): it is
+# NOT measured in this run, and the JSON line says so next to it.
+PROFILED_TRAFFIC = {"cfg4": (2.672e9, "profiles/cfg4_round_kernels.md"), "cfg5": (1.387e9, "profiles/cfg5_cfg3_round_kernels.md"),
+                    "cfg3": (1.364e8, "profiles/cfg5_cfg3_round_kernels.md")}
+# distinct resident input sets a run cycles through, so that no step finds its logits in the caches (cfg4's single set
+# is 22 times the 256 MB Infinity Cache); cfg5's sets are rounds 0..7 of the workload, each with its own draft lengths
+DEFAULT_SETS = {"cfg1": 8, "cfg2": 8, "cfg3": 4, "cfg4": 1, "cfg5": 8}
+DEFAULT_STEPS = {"cfg5": 100}            # the workload's 100 consecutive rounds
 
 
 def algorithmic_bytes(w, N, B):
@@ -41,12 +52,17 @@ def algorithmic_bytes(w, N, B):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=0, help="timed rounds (default 200; cfg5: its 100 consecutive rounds)")
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed steps first: the first twenty or so rounds after start-up run 5-10 %% slower")
     ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (debugging)")
+    ap.add_argument("--sets", type=int, default=0, help="distinct resident input sets to cycle through (default per config)")
     ap.add_argument("--cpu-seqs", type=int, default=-1, help="sequences in the oracle's timed sample (0 = skip)")
+    ap.add_argument("--burst", type=int, default=0,
+                    help="instead of the benchmark: after --burst-idle seconds of pause, this many compress calls back to back, "
+                         "each followed by a clock probe; prints the per-call duration and the shader clock behind it")
+    ap.add_argument("--burst-idle", type=float, default=2.0)
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -67,39 +83,82 @@ def main() -> int:
     if args.batch:
         w = w.scaled(B=args.batch)
 
-    t0 = time.time()
-    r = W.build_round(w, 0)
-    t_gen = time.time() - t0
-    B, N = r.B, r.N
+    steps = args.steps or DEFAULT_STEPS.get(args.config, 200)
+    n_sets = max(1, args.sets or DEFAULT_SETS[args.config])
+    n_sets = min(n_sets, steps)
 
     def to_dev(a):
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    draft, tgt = to_dev(r.draft_logits), to_dev(r.tgt_logits)
-    seq_off, uni, duni = to_dev(r.seq_off), to_dev(r.uniforms), to_dev(r.draft_uniforms)
-    q = ps.alloc_compressed(N, w.k, dev)
-    ver = ps.alloc_verified(B, N, dev)
-    res = ps.alloc_residual(B, dev)
+    # Input sets, all resident in HBM before anything is timed.  Set i is round i of the workload (cfg5: its own draft
+    # lengths, hence its own packing of the rows; the fixed-length workloads: the same logits in buffers of their own).
+    class InputSet:
+        pass
 
-    # untimed set-up: the drafter's tokens come from the compressed draft distributions
-    ps.compress(draft, w.V, w.T, w.k, w.top_p, out=q)
-    tok, _ = ps.sample_draft(q, duni)
+    t0 = time.time()
+    sets = []
+    for i in range(n_sets):
+        r = W.build_round(w, i)
+        x = InputSet()
+        x.round, x.B, x.N = r, r.B, r.N
+        x.draft, x.tgt = to_dev(r.draft_logits), to_dev(r.tgt_logits)
+        x.seq_off, x.duni = to_dev(r.seq_off), to_dev(r.draft_uniforms)
+        x.q = ps.alloc_compressed(r.N, w.k, dev)
+        x.ver = ps.alloc_verified(r.B, r.N, dev)
+        x.res = ps.alloc_residual(r.B, dev)
+        # untimed set-up: the drafter's tokens come from the compressed draft distributions
+        ps.compress(x.draft, w.V, w.T, w.k, w.top_p, out=x.q)
+        x.tok, _ = ps.sample_draft(x.q, x.duni)
+        if i:
+            x.round = None                   # (the host copy of set 0 alone is needed again, for round 0's uniforms)
+        sets.append(x)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+    B, N = sets[0].B, sets[0].N
+    # every timed round has uniforms of its own (round i of the workload's stream, cut to the set's row count)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.BASE_SEED + 7)
+    uniforms = [torch.rand(sets[i % n_sets].N + sets[i % n_sets].B, device=dev, generator=gen) for i in range(steps)]
+    uniforms[0] = to_dev(sets[0].round.uniforms)          # (round 0 exactly as the parity tests see it)
     torch.cuda.synchronize()
 
-    def step(ev=None, breakdown=False):
+    def step(i, ev=None, breakdown=False):
+        x, uni = sets[i % n_sets], uniforms[i % steps]
         if ev:
             ev[0].record()
-        ps.compress(draft, w.V, w.T, w.k, w.top_p, out=q)
+        ps.compress(x.draft, w.V, w.T, w.k, w.top_p, out=x.q)
         if ev:
             ev[1].record()
-        ps.verify(tgt, w.V, w.T, seq_off, N, tok, q, uni, out=ver)
+        ps.verify(x.tgt, w.V, w.T, x.seq_off, x.N, x.tok, x.q, uni, out=x.ver)
         if breakdown:
             ev[2].record()
-        ps.sample_residual(tgt, w.V, w.T, seq_off, N, ver, q, uni, out=res)
+        ps.sample_residual(x.tgt, w.V, w.T, x.seq_off, x.N, x.ver, x.q, uni, out=x.res)
         if breakdown:
             ev[3].record()
+
+    if args.burst:
+        # Where the slow first rounds come from: after a pause the device's effective shader clock dips for some tens
+        # of milliseconds (the compress kernel is bound by the vector ALU and follows it).
+        x = sets[0]
+        n = args.burst
+        ticks = torch.zeros((n, 2), dtype=torch.int64, device=dev)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
+        torch.cuda.synchronize()
+        time.sleep(args.burst_idle)
+        for i in range(n):
+            ev[i][0].record()
+            ps.compress(x.draft, w.V, w.T, w.k, w.top_p, out=x.q)
+            ev[i][1].record()
+            ps.probe_clock(ticks[i])
+        torch.cuda.synchronize()
+        tk = ticks.cpu().numpy().astype(np.float64)
+        print(f"# {w.name}: {n} compress calls back to back after {args.burst_idle} s of pause")
+        print("# call  start_ms  compress_us  shader_clock_MHz")
+        for i in range(n):
+            print(f"{i:5d}  {ev[0][0].elapsed_time(ev[i][0]):8.2f}  {ev[i][0].elapsed_time(ev[i][1]) * 1e3:11.1f}  {100.0 * tk[i, 0] / tk[i, 1]:8.0f}")
+        return 0
 
     if args.copy_probe_mib:
         src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -108,71 +167,103 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
+    clock_ticks = torch.zeros((2, 2), dtype=torch.int64, device=dev)
+    for i in range(args.warmup):
+        step(i)
+    ps.probe_clock(clock_ticks[0])           # the shader clock at the start of the timed region ...
     torch.cuda.synchronize()
-    # The timed region: K steps, each with one pair of events around the dominant kernel's call (every event
-    # between two kernels costs the round a few microseconds, so the other calls carry none here).
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    # The timed region: K consecutive rounds, each with one pair of events around the dominant kernel's call (every
+    # event between two kernels costs the round a few microseconds, so the other calls carry none here).
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i])
+    for i in range(steps):
+        step(i, events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_step = wall * 1e3 / args.steps
-    compress_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ps.probe_clock(clock_ticks[1])           # ... and at its end
+    torch.cuda.synchronize()
+    ck = clock_ticks.cpu().numpy().astype(np.float64)
+    clock_mhz = [float(100.0 * ck[j, 0] / ck[j, 1]) for j in range(2)]
+    ms_step = wall * 1e3 / steps
+    n_timed = sum(sets[i % n_sets].N for i in range(steps))               # draft positions verified in the timed region
+    compress_each = np.array([e[0].elapsed_time(e[1]) for e in events])
+    compress_ms = float(compress_each.mean())
     # per-step times from the same events (start of compress to start of the next step's compress)
-    step_ms = np.array([events[i][0].elapsed_time(events[i + 1][0]) for i in range(args.steps - 1)]) if args.steps > 1 else np.array([ms_step])
+    step_ms = np.array([events[i][0].elapsed_time(events[i + 1][0]) for i in range(steps - 1)]) if steps > 1 else np.array([ms_step])
 
     # After it, outside the timed region: a few more steps with events between all calls, for the per-call figures.
-    n_bd = max(1, min(args.steps, 10))
+    n_bd = max(1, min(steps, 10))
     bd_events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_bd)]
     for i in range(n_bd):
-        step(bd_events[i], breakdown=True)
+        step(i, bd_events[i], breakdown=True)
     torch.cuda.synchronize()
     call_ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in bd_events]).mean(axis=0)
 
-    # The same round through the one-call entry point (three launches at this size: the acceptance test and the
+    # The same rounds through the one-call entry point (three launches at the large sizes: the acceptance test and the
     # residual draw of a sequence share a workgroup), also outside the timed region.
-    n_oc = max(1, min(args.steps, 50))
+    n_oc = max(1, min(steps, 50))
     oc = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    ps.round(draft, tgt, w.V, w.T, seq_off, N, tok, w.k, uni, top_p=w.top_p, q=q, ver=ver, res=res)
+
+    def one_call(i):
+        x = sets[i % n_sets]
+        ps.round(x.draft, x.tgt, w.V, w.T, x.seq_off, x.N, x.tok, w.k, uniforms[i % steps], top_p=w.top_p, q=x.q, ver=x.ver, res=x.res)
+
+    one_call(0)
     oc[0].record()
-    for _ in range(n_oc):
-        ps.round(draft, tgt, w.V, w.T, seq_off, N, tok, w.k, uni, top_p=w.top_p, q=q, ver=ver, res=res)
+    for i in range(n_oc):
+        one_call(i)
     oc[1].record()
     torch.cuda.synchronize()
     one_call_ms = oc[0].elapsed_time(oc[1]) / n_oc
 
-    alg = algorithmic_bytes(w, N, B)
-    compress_gbs = alg["compress"] / (compress_ms * 1e-3) / 1e9
-    n_acc = ver.n_accept.cpu().numpy()
+    # algorithmic bytes: of the timed region (the sets differ in their row counts) and of the breakdown steps
+    alg_steps = [algorithmic_bytes(w, sets[i % n_sets].N, sets[i % n_sets].B) for i in range(steps)]
+    alg_total = sum(a["total"] for a in alg_steps)
+    alg_compress = sum(a["compress"] for a in alg_steps)
+    alg_bd = {k: float(np.mean([algorithmic_bytes(w, sets[i % n_sets].N, sets[i % n_sets].B)[k] for i in range(n_bd)]))
+              for k in ("compress", "verify", "residual")}
+    compress_gbs = alg_compress / (compress_each.sum() * 1e-3) / 1e9
+    n_acc = sets[0].ver.n_accept.cpu().numpy()
+    set_bytes = (sets[0].draft.numel() + sets[0].tgt.numel()) * sets[0].draft.element_size()
+    cache_resident = n_sets * set_bytes < 2 * 256e6          # (all sets together within reach of the 256 MB Infinity Cache)
+    traffic = PROFILED_TRAFFIC.get(args.config)
+    head = max(1, min(5, steps // 4))
 
     out = {
         "metric": "verified draft positions/sec (compress + verify + sample_residual, 1 GPU)",
-        "value": N / (ms_step * 1e-3),
+        "value": n_timed / (wall),
         "unit": "positions/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={B} gamma={w.gamma_lo}..{w.gamma_hi} V={w.V} {w.dtype} T={w.T} "
-                               f"k={w.k} top_p={w.top_p}", "draft_rows": N, "target_rows": N + B,
-                   "parallelism": "1 GPU"},
-        "round_algorithmic_GBps": alg["total"] / (ms_step * 1e-3) / 1e9,
-        "round_frac_of_hbm_peak": alg["total"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                               f"k={w.k} top_p={w.top_p}", "draft_rows": N if n_sets == 1 else [x.N for x in sets],
+                   "target_rows": N + B if n_sets == 1 else [x.N + x.B for x in sets],
+                   "input_sets": n_sets, "protocol": f"{steps} consecutive rounds over {n_sets} resident input set(s), "
+                   "uniforms of its own for every round", "parallelism": "1 GPU"},
+        "round_algorithmic_GBps": alg_total / wall / 1e9,
+        "round_frac_of_hbm_peak": None if cache_resident else alg_total / wall / 1e9 / HBM_PEAK_GBS,
+        "cache_resident": bool(cache_resident),
         "step_ms": {"median": float(np.median(step_ms)), "min": float(step_ms.min()), "max": float(step_ms.max())},
         "compress_ms": compress_ms,
+        "compress_ms_first_last": {"first": float(compress_each[:head].mean()), "last": float(compress_each[-head:].mean()),
+                                   "note": f"mean of the first and of the last {head} timed rounds: for some tens of milliseconds after a "
+                                           "pause the device's effective shader clock dips (bench.py --burst shows it)"},
+        "shader_clock_mhz": {"before_timed": clock_mhz[0], "after_timed": clock_mhz[1],
+                             "note": "s_memtime / s_memrealtime over a fixed loop (picospec_probe_clock)"},
         "one_call_ms": one_call_ms,
         "call_ms": {"compress": float(call_ms[0]), "verify": float(call_ms[1]), "sample_residual": float(call_ms[2]),
                     "note": f"{n_bd} extra steps after the timed region, events between all calls"},
-        "call_GBps": {"compress": alg["compress"] / (call_ms[0] * 1e-3) / 1e9,
-                      "verify": alg["verify"] / (call_ms[1] * 1e-3) / 1e9,
-                      "sample_residual": alg["residual"] / (call_ms[2] * 1e-3) / 1e9},
+        "call_GBps": {"compress": alg_bd["compress"] / (call_ms[0] * 1e-3) / 1e9,
+                      "verify": alg_bd["verify"] / (call_ms[1] * 1e-3) / 1e9,
+                      "sample_residual": alg_bd["residual"] / (call_ms[2] * 1e-3) / 1e9},
         "mean_accepted": float(n_acc.mean()),
         "input_generation_s": t_gen,
         "roofline": {"kernel": "compress_kernel", "bound": "hbm", "achieved": compress_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": compress_gbs / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get(args.config)},
+                     "traffic": traffic[0] if traffic else None,
+                     "traffic_source": (traffic[1] + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                                        "command; a constant here, not measured in this run)") if traffic else None},
     }
 
     # the CPU oracle, as it stands, on a bounded sample of the same workload
@@ -180,7 +271,7 @@ def main() -> int:
     if n_cpu > 0:
         import oracle
         sub = W.build_round(w, 0, seqs=range(n_cpu))
-        tok_sub = tok.cpu().numpy()[: sub.N]       # same drafted tokens (prefix of the batch)
+        tok_sub = sets[0].tok.cpu().numpy()[: sub.N]       # same drafted tokens (prefix of the batch)
         t0 = time.perf_counter()
         oq = oracle.compress(sub.draft_logits, w.V, w.T, w.k, w.top_p)
         ov = oracle.verify(sub.tgt_logits, w.V, w.T, sub.seq_off, tok_sub, oq, sub.uniforms)

@@ -346,6 +346,15 @@ int64_t picospec_max_load_byte(int which_call, int dtype, int32_t V, int32_t mis
  */
 int picospec_check_device(void* workspace, size_t workspace_bytes, uint32_t* status, void* stream);
 
+/*
+ * Measurement aid (enqueues one single-wave kernel of about 10 microseconds): ticks[0] = shader-clock cycles and
+ * ticks[1] = ticks of the constant 100 MHz wall clock over the same fixed loop, so that 100 * ticks[0] / ticks[1] is the
+ * shader clock in MHz that the device runs at when the stream reaches this point.  The kernels of the hot path that are
+ * bound by the vector ALU follow that clock; after a pause in the work it dips for some tens of milliseconds.
+ *   ticks  device, two uint64 on an 8-byte boundary   out
+ */
+int picospec_probe_clock(uint64_t* ticks, void* stream);
+
 /* host: bytes of device workspace the given call needs for (dtype, rows, V, k); 0 if none. */
 size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k);
 

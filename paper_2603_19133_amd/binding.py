@@ -26,7 +26,7 @@ WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 EXPORTS = ("picospec_round", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
-           "picospec_downlink_bytes_max", "picospec_uplink_bytes", "picospec_max_load_byte", "picospec_check_device",
+           "picospec_downlink_bytes_max", "picospec_uplink_bytes", "picospec_max_load_byte", "picospec_check_device", "picospec_probe_clock",
            "picospec_workspace_bytes", "picospec_limit", "picospec_strerror", "picospec_version")
 
 if not os.path.exists(LIB_PATH):
@@ -63,6 +63,8 @@ lib.picospec_max_load_byte.argtypes = [C.c_int, C.c_int, _i32, _i32]
 lib.picospec_max_load_byte.restype = _i64
 lib.picospec_check_device.argtypes = [_p, _sz, _p, _p]
 lib.picospec_check_device.restype = C.c_int
+lib.picospec_probe_clock.argtypes = [_p, _p]
+lib.picospec_probe_clock.restype = C.c_int
 lib.picospec_workspace_bytes.argtypes = [C.c_int, C.c_int, _i32, _i32, _i32]
 lib.picospec_workspace_bytes.restype = _sz
 lib.picospec_limit.argtypes = [C.c_int]
@@ -367,6 +369,11 @@ def check_device(device) -> int:
     status = torch.full((1,), -1, dtype=torch.int32, device=device)
     _check(lib.picospec_check_device(_ptr(ws), ws.numel(), _ptr(status), _stream()))
     return int(status.item()) & 0xFFFFFFFF
+
+
+def probe_clock(ticks: torch.Tensor) -> None:
+    """picospec_probe_clock into `ticks` (int64 [2], device): 100 * ticks[0] / ticks[1] = shader clock in MHz."""
+    _check(lib.picospec_probe_clock(_ptr(ticks), _stream()))
 
 
 def max_load_byte(which: int, dtype: int, V: int, misalign_bytes: int) -> int:

@@ -372,6 +372,12 @@ int picospec_check_device(void* workspace, size_t workspace_bytes, uint32_t* sta
     return hip_status(launch_check_device(workspace, status, (hipStream_t)stream));
 }
 
+int picospec_probe_clock(uint64_t* ticks, void* stream)
+{
+    if (!ticks || ((uintptr_t)ticks & 7u)) return PICOSPEC_EINVAL;
+    return hip_status(launch_probe_clock(ticks, (hipStream_t)stream));
+}
+
 int64_t picospec_limit(int which)
 {
     switch (which) {

@@ -113,6 +113,7 @@ hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t l
 // device self-check of the buffer loads' range check (csrc/selfcheck.hip); the workspace holds kCheckBytes
 constexpr int kCheckBytes = 64 * 1024;
 hipError_t launch_check_device(void* workspace, uint32_t* status, hipStream_t stream);
+hipError_t launch_probe_clock(uint64_t* out, hipStream_t stream);
 
 // ---- wire messages (csrc/wire.hip); fmt: 0 fp32, 1 fp16, 2 bf16 probabilities
 int64_t downlink_bytes_max(int B, int k, int fmt);

@@ -38,7 +38,25 @@ __global__ __launch_bounds__(kWave) void check_range_kernel(const uint32_t* __re
     if (bad) atomicOr(status, bad);
 }
 
+// One wave: a fixed loop of dependent fused multiply-adds, timed with the shader-clock counter (s_memtime) and with
+// the constant 100 MHz wall clock (s_memrealtime).  Their ratio is the shader clock the device really runs at.
+__global__ __launch_bounds__(kWave) void probe_clock_kernel(uint64_t* __restrict__ out)
+{
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    float a = (float)threadIdx.x * 1e-3f;
+    for (int i = 0; i < 4000; ++i) a = fmaf(a, 1.0001f, 0.5f);
+    const unsigned long long c1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+    if (a == 12345.678f) out[1] = 0;             // (keeps the loop)
+}
+
 }  // namespace
+
+hipError_t launch_probe_clock(uint64_t* out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(probe_clock_kernel, dim3(1), dim3(kWave), 0, stream, out);
+    return hipGetLastError();
+}
 
 hipError_t launch_check_device(void* workspace, uint32_t* status, hipStream_t stream)
 {

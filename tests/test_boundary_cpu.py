@@ -319,3 +319,8 @@ def test_check_device_rejects_misuse(B):
     assert f(FAKE, 1 << 16, None, None) == B.EINVAL
     assert f(FAKE, (1 << 16) - 1, FAKE, None) == B.EINVAL          # workspace too small
     assert f(FAKE + 4, 1 << 16, FAKE, None) == B.EINVAL             # not on a 16-byte boundary
+
+
+def test_probe_clock_rejects_misuse(B):
+    assert B.lib.picospec_probe_clock(None, None) == B.EINVAL
+    assert B.lib.picospec_probe_clock(FAKE + 4, None) == B.EINVAL
