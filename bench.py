@@ -39,13 +39,18 @@ DEFAULT_SETS = {"cfg1": 8, "cfg2": 8, "cfg3": 4, "cfg4": 1, "cfg5": 8}
 DEFAULT_STEPS = {"cfg5": 100}            # the workload's 100 consecutive rounds
 
 
-def algorithmic_bytes(w, N, B):
-    """Bytes the method has to move once (the roofline numerator), per call."""
+def algorithmic_bytes(w, N, B, seg_table_bytes=0):
+    """Bytes the method has to move once (the roofline numerator), per call.  With the segment table the draw does not
+    read its target row again: it reads the record, one gathered logit per record entry, its row of the table and one
+    segment of at most 4 KB; the table itself is written once by verify."""
     e = 4 if w.dtype == "f32" else 2
     rec = N * w.k * 8                       # sparse records: int32 id + fp32 prob
     compress = N * w.V * e + rec + N * 12   # rows read once, records + count/mass/lse written once
-    verify = (N + B) * w.V * e + rec + (N + B) * 12 + N * 16
-    residual = B * (w.V * e + w.k * 8)      # one target row per sequence re-read, one record
+    verify = (N + B) * w.V * e + rec + (N + B) * 12 + N * 16 + seg_table_bytes
+    if seg_table_bytes:
+        residual = B * (w.k * 8 + w.k * e + 4096 + seg_table_bytes // max(1, N + B))
+    else:
+        residual = B * (w.V * e + w.k * 8)  # one target row per sequence re-read, one record
     return dict(compress=compress, verify=verify, residual=residual, total=compress + verify + residual)
 
 
@@ -63,6 +68,8 @@ def main() -> int:
                     help="instead of the benchmark: after --burst-idle seconds of pause, this many compress calls back to back, "
                          "each followed by a clock probe; prints the per-call duration and the shader clock behind it")
     ap.add_argument("--burst-idle", type=float, default=2.0)
+    ap.add_argument("--no-workspace", action="store_true",
+                    help="run verify / sample_residual without the optional workspace (the draw then streams its target row again)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -108,6 +115,8 @@ def main() -> int:
         x.q = ps.alloc_compressed(r.N, w.k, dev)
         x.ver = ps.alloc_verified(r.B, r.N, dev)
         x.res = ps.alloc_residual(r.B, dev)
+        x.ws = None if args.no_workspace else ps.alloc_workspace(x.tgt.dtype, r.N + r.B, w.V, dev)
+        x.ws_bytes = 0 if x.ws is None else x.ws.numel()
         # untimed set-up: the drafter's tokens come from the compressed draft distributions
         ps.compress(x.draft, w.V, w.T, w.k, w.top_p, out=x.q)
         x.tok, _ = ps.sample_draft(x.q, x.duni)
@@ -131,10 +140,10 @@ def main() -> int:
         ps.compress(x.draft, w.V, w.T, w.k, w.top_p, out=x.q)
         if ev:
             ev[1].record()
-        ps.verify(x.tgt, w.V, w.T, x.seq_off, x.N, x.tok, x.q, uni, out=x.ver)
+        ps.verify(x.tgt, w.V, w.T, x.seq_off, x.N, x.tok, x.q, uni, out=x.ver, workspace=x.ws)
         if breakdown:
             ev[2].record()
-        ps.sample_residual(x.tgt, w.V, w.T, x.seq_off, x.N, x.ver, x.q, uni, out=x.res)
+        ps.sample_residual(x.tgt, w.V, w.T, x.seq_off, x.N, x.ver, x.q, uni, out=x.res, workspace=x.ws)
         if breakdown:
             ev[3].record()
 
@@ -206,7 +215,8 @@ def main() -> int:
 
     def one_call(i):
         x = sets[i % n_sets]
-        ps.round(x.draft, x.tgt, w.V, w.T, x.seq_off, x.N, x.tok, w.k, uniforms[i % steps], top_p=w.top_p, q=x.q, ver=x.ver, res=x.res)
+        ps.round(x.draft, x.tgt, w.V, w.T, x.seq_off, x.N, x.tok, w.k, uniforms[i % steps], top_p=w.top_p, q=x.q, ver=x.ver, res=x.res,
+                 workspace=x.ws)
 
     one_call(0)
     oc[0].record()
@@ -217,10 +227,10 @@ def main() -> int:
     one_call_ms = oc[0].elapsed_time(oc[1]) / n_oc
 
     # algorithmic bytes: of the timed region (the sets differ in their row counts) and of the breakdown steps
-    alg_steps = [algorithmic_bytes(w, sets[i % n_sets].N, sets[i % n_sets].B) for i in range(steps)]
+    alg_steps = [algorithmic_bytes(w, sets[i % n_sets].N, sets[i % n_sets].B, sets[i % n_sets].ws_bytes) for i in range(steps)]
     alg_total = sum(a["total"] for a in alg_steps)
     alg_compress = sum(a["compress"] for a in alg_steps)
-    alg_bd = {k: float(np.mean([algorithmic_bytes(w, sets[i % n_sets].N, sets[i % n_sets].B)[k] for i in range(n_bd)]))
+    alg_bd = {k: float(np.mean([algorithmic_bytes(w, sets[i % n_sets].N, sets[i % n_sets].B, sets[i % n_sets].ws_bytes)[k] for i in range(n_bd)]))
               for k in ("compress", "verify", "residual")}
     compress_gbs = alg_compress / (compress_each.sum() * 1e-3) / 1e9
     n_acc = sets[0].ver.n_accept.cpu().numpy()
@@ -239,7 +249,7 @@ def main() -> int:
         "config": {"workload": f"{w.name}: B={B} gamma={w.gamma_lo}..{w.gamma_hi} V={w.V} {w.dtype} T={w.T} "
                                f"k={w.k} top_p={w.top_p}", "draft_rows": N if n_sets == 1 else [x.N for x in sets],
                    "target_rows": N + B if n_sets == 1 else [x.N + x.B for x in sets],
-                   "input_sets": n_sets, "protocol": f"{steps} consecutive rounds over {n_sets} resident input set(s), "
+                   "input_sets": n_sets, "segment_table": not args.no_workspace, "protocol": f"{steps} consecutive rounds over {n_sets} resident input set(s), "
                    "uniforms of its own for every round", "parallelism": "1 GPU"},
         "round_algorithmic_GBps": alg_total / wall / 1e9,
         "round_frac_of_hbm_peak": None if cache_resident else alg_total / wall / 1e9 / HBM_PEAK_GBS,

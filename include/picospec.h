@@ -37,6 +37,13 @@
  *     the raw probability P(id), not renormalised), ordered by (logit descending, id ascending);
  *     count used slots, the rest hold idx = -1, prob = 0; mass = sum of the kept prob.
  *     8 bytes per kept component, as in the paper's payload arithmetic.
+ *   - Workspace: optional everywhere (NULL: the call works without it).  picospec_verify, picospec_verify_sample and
+ *     picospec_round can keep the target rows' SEGMENT TABLE in it: the sum of exp((z - M)/T) over every 2 or 4 KB of
+ *     every target row, which the statistics pass has at hand anyway.  With it the correction / bonus draw
+ *     (picospec_sample_residual given the SAME workspace that picospec_verify filled for the same rows, or the draw
+ *     inside the fused calls) does not stream its target row a second time: it gathers one logit per record entry
+ *     and reads the one segment in which the draw falls.  Size: picospec_workspace_bytes(call, dtype, n_draft + B, V, k)
+ *     bytes on a 16-byte boundary (about 1.2 KB per target row at V = 152 K); its content is the library's business.
  *   - Return value: PICOSPEC_OK or a negative PICOSPEC_E* code.  Misuse that the host can see
  *     (null pointers, sizes, dtype, workspace) is rejected BEFORE anything is launched.
  *     Data-dependent conditions never fail a call; they set bits in `flags`.
@@ -62,7 +69,7 @@ enum { PICOSPEC_F32 = 0, PICOSPEC_BF16 = 1 };
 enum {
     PICOSPEC_OK = 0,
     PICOSPEC_EINVAL = -1,      /* null pointer, size out of range, bad temperature ... */
-    PICOSPEC_EWORKSPACE = -2,  /* workspace smaller than picospec_workspace_bytes() says */
+    PICOSPEC_EWORKSPACE = -2,  /* a workspace was given that is smaller than picospec_workspace_bytes() says, or misaligned */
     PICOSPEC_EDTYPE = -3,      /* dtype is neither PICOSPEC_F32 nor PICOSPEC_BF16 */
     PICOSPEC_EHIP = -4,        /* a HIP runtime call (launch, attribute) failed */
     PICOSPEC_EUNSUPPORTED = -5 /* k or V beyond the limits reported by picospec_limit() */
@@ -78,7 +85,8 @@ enum {
 };
 
 enum { PICOSPEC_CALL_COMPRESS = 0, PICOSPEC_CALL_SAMPLE_DRAFT = 1, PICOSPEC_CALL_VERIFY = 2, PICOSPEC_CALL_SAMPLE_RESIDUAL = 3,
-       PICOSPEC_CALL_COMPRESS_REJECTED = 4, PICOSPEC_CALL_RESAMPLE_SPARSE = 5 };
+       PICOSPEC_CALL_COMPRESS_REJECTED = 4, PICOSPEC_CALL_RESAMPLE_SPARSE = 5, PICOSPEC_CALL_ROUND = 6,
+       PICOSPEC_CALL_VERIFY_SAMPLE = 7 };
 enum { PICOSPEC_LIMIT_MAX_K = 0, PICOSPEC_LIMIT_MAX_V = 1 };
 
 /*
@@ -92,7 +100,7 @@ enum { PICOSPEC_LIMIT_MAX_K = 0, PICOSPEC_LIMIT_MAX_V = 1 };
  *          order whose probability sum reaches top_p, capped at k (a workload setting, not in the paper)
  *   idx [n_rows,k] int32, prob [n_rows,k] fp32, count [n_rows] int32, mass [n_rows] fp32,
  *   lse [n_rows] fp32             out
- *   workspace: picospec_workspace_bytes(PICOSPEC_CALL_COMPRESS, ...) bytes, may be NULL when that is 0.
+ *   workspace: unused (picospec_workspace_bytes(PICOSPEC_CALL_COMPRESS, ...) is 0); pass NULL.
  */
 int picospec_compress(const void* logits, int dtype, int64_t ld, int32_t n_rows, int32_t V,
                       float temperature, int32_t k, float top_p,
@@ -250,6 +258,22 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Verification and draw in one call on records that exist (Section 3.3: the cloud's part of a round when the drafter
+ * has compressed its distributions, drawn from them and sent records and tokens): picospec_verify followed by
+ * picospec_sample_residual, with the same arguments, outputs and flags, as two launches (the statistics of the target
+ * rows; acceptance and draw of a sequence in one workgroup, so the rejected position never leaves it).  Nothing is
+ * compressed here: unlike picospec_round the call takes the records the drafted tokens were drawn from.
+ */
+int picospec_verify_sample(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                           int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                           const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                           int32_t k, int renorm, const float* uniforms,
+                           int32_t* n_accept, float* p_tok, float* q_tok,
+                           float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* verify_flags,
+                           int32_t* out_tok, float* resid_mass, uint32_t* residual_flags,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ---- Wire messages of a round (Section 3.3) ----------------------------------------------------
  * Uplink (edge -> cloud): the drafted tokens and only their own probabilities q_1..q_gamma, 8 bytes
  * per drafted token with fp32 probabilities (48 bytes at gamma = 6).  Downlink (cloud -> edge): per
@@ -355,7 +379,8 @@ int picospec_check_device(void* workspace, size_t workspace_bytes, uint32_t* sta
  */
 int picospec_probe_clock(uint64_t* ticks, void* stream);
 
-/* host: bytes of device workspace the given call needs for (dtype, rows, V, k); 0 if none. */
+/* host: bytes of the optional device workspace of the given call for (dtype, rows, V, k), rows = n_draft + B for the
+ * calls that take target rows; 0 if the call has no use for one. */
 size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k);
 
 /* host: largest supported k (PICOSPEC_LIMIT_MAX_K) or V (PICOSPEC_LIMIT_MAX_V); -1 for an unknown id. */

@@ -19,11 +19,12 @@ F32, BF16 = 0, 1
 OK, EINVAL, EWORKSPACE, EDTYPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 FLAG_TOKEN_NOT_IN_SUPPORT, FLAG_NONFINITE, FLAG_RESIDUAL_EMPTY, FLAG_BAD_INPUT = 1, 2, 4, 8
 CALL_COMPRESS, CALL_SAMPLE_DRAFT, CALL_VERIFY, CALL_SAMPLE_RESIDUAL = 0, 1, 2, 3
+CALL_ROUND, CALL_VERIFY_SAMPLE = 6, 7
 LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
 WIRE_FP32, WIRE_FP16, WIRE_BF16 = 0, 1, 2
 WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 
-EXPORTS = ("picospec_round", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
+EXPORTS = ("picospec_round", "picospec_verify_sample", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
            "picospec_downlink_bytes_max", "picospec_uplink_bytes", "picospec_max_load_byte", "picospec_check_device", "picospec_probe_clock",
@@ -44,6 +45,9 @@ lib.picospec_verify_range.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _
                                       _p, _p, _p, _p, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_round.argtypes = [_p, _p, C.c_int, _i64, _i64, _i32, _f, _i32, _i32, _p, _p, _i32, _f, C.c_int, _p,
                                _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_verify_sample.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int, _p,
+                                       _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
+lib.picospec_verify_sample.restype = C.c_int
 lib.picospec_sample_residual.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
                                          _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_row_stats.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _p, _p, _p, _p]
@@ -91,6 +95,17 @@ def _check(rc: int) -> None:
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def alloc_workspace(dtype: torch.dtype, rows: int, V: int, device, which: int = CALL_VERIFY) -> torch.Tensor:
+    """The optional workspace of verify / sample_residual / verify_sample / round for `rows` = n_draft + B target rows."""
+    code = F32 if dtype == torch.float32 else BF16
+    n = int(lib.picospec_workspace_bytes(which, code, rows, V, 0))
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
 
 
 def _stream():
@@ -171,8 +186,10 @@ def alloc_verified(B: int, N: int, device) -> Verified:
 
 def verify(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
            draft_tok: torch.Tensor, q: Compressed | None, uniforms: torch.Tensor, renorm: int = 1,
-           q_scalar: torch.Tensor | None = None, out: Verified | None = None) -> Verified:
-    """picospec_verify; seq_off int32 [B+1] on device, n_draft = seq_off[B] known on the host."""
+           q_scalar: torch.Tensor | None = None, out: Verified | None = None,
+           workspace: torch.Tensor | None = None) -> Verified:
+    """picospec_verify; seq_off int32 [B+1] on device, n_draft = seq_off[B] known on the host.  `workspace`
+    (alloc_workspace) receives the target rows' segment table for sample_residual."""
     dt, ld = _logits_2d(tgt_logits)
     B = seq_off.shape[0] - 1
     out = out or alloc_verified(B, n_draft, tgt_logits.device)
@@ -182,7 +199,7 @@ def verify(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.
                                q.k if q else 0, renorm, _ptr(q_scalar), _ptr(uniforms),
                                _ptr(out.n_accept), _ptr(out.p_tok), _ptr(out.q_tok),
                                _ptr(out.tgt_max), _ptr(out.tgt_sum), _ptr(out.tgt_lse), _ptr(out.flags),
-                               None, 0, _stream()))
+                               _ptr(workspace), _nbytes(workspace), _stream()))
     return out
 
 
@@ -208,7 +225,8 @@ def verify_range(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: 
 
 def round(draft_logits: torch.Tensor, tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor,
           n_draft: int, draft_tok: torch.Tensor, k: int, uniforms: torch.Tensor, top_p: float = 0.0, renorm: int = 1,
-          q: "Compressed | None" = None, ver: "Verified | None" = None, res: "Residual | None" = None):
+          q: "Compressed | None" = None, ver: "Verified | None" = None, res: "Residual | None" = None,
+          workspace: torch.Tensor | None = None):
     """picospec_round -> (Compressed, Verified, Residual): the whole round in one call."""
     dt, ld_d = _logits_2d(draft_logits) if n_draft else (_dtype_code(tgt_logits), V)
     dt_t, ld_t = _logits_2d(tgt_logits)
@@ -224,8 +242,27 @@ def round(draft_logits: torch.Tensor, tgt_logits: torch.Tensor, V: int, temperat
                               _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), _ptr(q.lse),
                               _ptr(ver.n_accept), _ptr(ver.p_tok), _ptr(ver.q_tok),
                               _ptr(ver.tgt_max), _ptr(ver.tgt_sum), _ptr(ver.tgt_lse), _ptr(ver.flags),
-                              _ptr(res.out_tok), _ptr(res.resid_mass), _ptr(res.flags), None, 0, _stream()))
+                              _ptr(res.out_tok), _ptr(res.resid_mass), _ptr(res.flags),
+                              _ptr(workspace), _nbytes(workspace), _stream()))
     return q, ver, res
+
+
+def verify_sample(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+                  draft_tok: torch.Tensor, q: "Compressed", uniforms: torch.Tensor, renorm: int = 1,
+                  ver: "Verified | None" = None, res: "Residual | None" = None, workspace: torch.Tensor | None = None):
+    """picospec_verify_sample -> (Verified, Residual): verification and draw on records that exist."""
+    dt, ld = _logits_2d(tgt_logits)
+    B = seq_off.shape[0] - 1
+    dev = tgt_logits.device
+    ver = ver or alloc_verified(B, n_draft, dev)
+    res = res or alloc_residual(B, dev)
+    _check(lib.picospec_verify_sample(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off), _ptr(draft_tok),
+                                      _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), q.k, renorm, _ptr(uniforms),
+                                      _ptr(ver.n_accept), _ptr(ver.p_tok), _ptr(ver.q_tok),
+                                      _ptr(ver.tgt_max), _ptr(ver.tgt_sum), _ptr(ver.tgt_lse), _ptr(ver.flags),
+                                      _ptr(res.out_tok), _ptr(res.resid_mass), _ptr(res.flags),
+                                      _ptr(workspace), _nbytes(workspace), _stream()))
+    return ver, res
 
 
 @dataclass
@@ -243,8 +280,10 @@ def alloc_residual(B: int, device) -> Residual:
 
 def sample_residual(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
                     ver: Verified, q: Compressed, uniforms: torch.Tensor, renorm: int = 1,
-                    out: Residual | None = None, n_accept: torch.Tensor | None = None) -> Residual:
-    """picospec_sample_residual from the statistics and first-rejection indices of `ver`."""
+                    out: Residual | None = None, n_accept: torch.Tensor | None = None,
+                    workspace: torch.Tensor | None = None) -> Residual:
+    """picospec_sample_residual from the statistics and first-rejection indices of `ver` (and, if given, from the
+    segment table that verify left in `workspace`)."""
     dt, ld = _logits_2d(tgt_logits)
     B = seq_off.shape[0] - 1
     out = out or alloc_residual(B, tgt_logits.device)
@@ -253,7 +292,7 @@ def sample_residual(tgt_logits: torch.Tensor, V: int, temperature: float, seq_of
                                         _ptr(ver.tgt_max), _ptr(ver.tgt_sum),
                                         _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), q.k, renorm,
                                         _ptr(uniforms), _ptr(out.out_tok), _ptr(out.resid_mass), _ptr(out.flags),
-                                        None, 0, _stream()))
+                                        _ptr(workspace), _nbytes(workspace), _stream()))
     return out
 
 

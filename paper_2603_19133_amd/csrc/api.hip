@@ -25,10 +25,11 @@ int check_logits(const void* logits, int dtype, int64_t ld, int64_t rows, int32_
     return PICOSPEC_OK;
 }
 
+// The workspace is optional: a call that is given none works without it.  One that is too small is an error.
 int check_workspace(int which, int dtype, int64_t rows, int32_t V, int32_t k, const void* ws, size_t ws_bytes)
 {
-    const size_t need = picospec_workspace_bytes(which, dtype, (int32_t)rows, V, k);
-    if (need && (!ws || ws_bytes < need)) return PICOSPEC_EWORKSPACE;
+    if (!ws) return PICOSPEC_OK;
+    if (((uintptr_t)ws & 15u) || ws_bytes < picospec_workspace_bytes(which, dtype, (int32_t)rows, V, k)) return PICOSPEC_EWORKSPACE;
     return PICOSPEC_OK;
 }
 
@@ -92,7 +93,7 @@ int picospec_row_stats(const void* logits, int dtype, int64_t ld, int32_t n_rows
     if (int rc = check_logits(logits, dtype, ld, n_rows, V, temperature)) return rc;
     if (n_rows > 0 && (!row_max || !row_sum)) return PICOSPEC_EINVAL;
     return hip_status(launch_row_stats(logits, dtype, ld, n_rows, V, temperature, row_max, row_sum, row_lse,
-                                       (hipStream_t)stream));
+                                       nullptr, (hipStream_t)stream));
 }
 
 int picospec_compress_rejected(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
@@ -146,7 +147,6 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
                    int32_t* out_tok, float* resid_mass, uint32_t* residual_flags,
                    void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
     const int64_t rows = (int64_t)n_draft + B;
     if (rows > INT32_MAX) return PICOSPEC_EINVAL;
@@ -157,12 +157,15 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
     if (n_draft > 0 && (!draft_tok || !q_idx || !q_prob || !q_count || !q_mass || !q_lse)) return PICOSPEC_EINVAL;
     if (B > 0 && (!seq_off || !uniforms || !n_accept || !verify_flags || !tgt_max || !tgt_sum || !out_tok ||
                   !resid_mass || !residual_flags)) return PICOSPEC_EINVAL;
+    if (int rc = check_workspace(PICOSPEC_CALL_ROUND, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
     hipStream_t s = (hipStream_t)stream;
     // The two per-sequence kernels always go out as one (the position found by the acceptance test never leaves
     // the workgroup).  A round that leaves most of the chip idle is bound by the serial part of each launch, so
     // its two streaming kernels go out as one as well; a round that fills the chip streams faster with each
     // kernel in its own launch shape.
-    if (rows + n_draft <= kRoundSmallRows) {
+    const bool small_round = rows + n_draft <= kRoundSmallRows;     // (bound by its launches: two of them, and no use for the table)
+    if (small_round) workspace = nullptr;
+    if (small_round) {
         if (hipError_t e = launch_round_stream(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx,
                                                q_prob, q_count, q_mass, q_lse, tgt_logits, ld_tgt, (int)rows,
                                                tgt_max, tgt_sum, tgt_lse, s))
@@ -171,12 +174,41 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
         if (hipError_t e = launch_compress(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx, q_prob,
                                            q_count, q_mass, q_lse, nullptr, nullptr, s))
             return hip_status(e);
-        if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld_tgt, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s))
+        if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld_tgt, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, workspace, s))
             return hip_status(e);
     }
     return hip_status(launch_decide(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
                                     q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
-                                    verify_flags, out_tok, resid_mass, residual_flags, s));
+                                    verify_flags, out_tok, resid_mass, residual_flags, workspace, rows, s));
+}
+
+// ---- verification and draw on records that exist
+
+int picospec_verify_sample(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                           int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                           const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                           int32_t k, int renorm, const float* uniforms,
+                           int32_t* n_accept, float* p_tok, float* q_tok,
+                           float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* verify_flags,
+                           int32_t* out_tok, float* resid_mass, uint32_t* residual_flags,
+                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || n_draft < 0) return PICOSPEC_EINVAL;
+    const int64_t rows = (int64_t)n_draft + B;
+    if (rows > INT32_MAX) return PICOSPEC_EINVAL;
+    if (int rc = check_logits(tgt_logits, dtype, ld, rows, V, temperature)) return rc;
+    if (renorm != 0 && renorm != 1) return PICOSPEC_EINVAL;
+    if (n_draft > 0 && (k < 1 || !draft_tok || !q_idx || !q_prob || !q_count || !q_mass)) return PICOSPEC_EINVAL;
+    if (n_draft > 0 && k > kMaxK) return PICOSPEC_EUNSUPPORTED;
+    if (B > 0 && (!seq_off || !uniforms || !n_accept || !verify_flags || !tgt_max || !tgt_sum || !out_tok ||
+                  !resid_mass || !residual_flags)) return PICOSPEC_EINVAL;
+    if (int rc = check_workspace(PICOSPEC_CALL_VERIFY_SAMPLE, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipError_t e = launch_row_stats(tgt_logits, dtype, ld, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, workspace, s))
+        return hip_status(e);
+    return hip_status(launch_decide(tgt_logits, dtype, ld, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
+                                    q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
+                                    verify_flags, out_tok, resid_mass, residual_flags, workspace, rows, s));
 }
 
 // ---- wire messages
@@ -289,7 +321,7 @@ int verify_impl(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float 
     const hipError_t e = ranged
         ? launch_row_stats_range(tgt_logits, dtype, ld, V, temperature, B, gamma_max, seq_off, pos_begin, pos_end,
                                  tgt_max, tgt_sum, tgt_lse, s)
-        : launch_row_stats(tgt_logits, dtype, ld, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, s);
+        : launch_row_stats(tgt_logits, dtype, ld, (int)rows, V, temperature, tgt_max, tgt_sum, tgt_lse, workspace, s);
     if (e != hipSuccess) return hip_status(e);
     return hip_status(launch_accept(tgt_logits, dtype, ld, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
                                     q_count, q_mass, k, renorm, q_scalar, uniforms, tgt_max, tgt_sum,
@@ -346,13 +378,19 @@ int picospec_sample_residual(const void* tgt_logits, int dtype, int64_t ld, int3
     if (int rc = check_workspace(PICOSPEC_CALL_SAMPLE_RESIDUAL, dtype, rows, V, k, workspace, workspace_bytes)) return rc;
     return hip_status(launch_residual(tgt_logits, dtype, ld, V, temperature, B, seq_off, n_accept, tgt_max, tgt_sum,
                                       q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass,
-                                      flags, (hipStream_t)stream));
+                                      flags, workspace, rows, (hipStream_t)stream));
 }
 
 size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t V, int32_t k)
 {
-    (void)which_call; (void)dtype; (void)rows; (void)V; (void)k;
-    return 0;   // every kernel keeps its intermediate state in LDS
+    (void)k;
+    if (rows < 0 || V < 1 || V > kMaxV) return 0;
+    switch (which_call) {                       // the calls that can keep the target rows' segment table
+        case PICOSPEC_CALL_VERIFY: case PICOSPEC_CALL_SAMPLE_RESIDUAL: case PICOSPEC_CALL_ROUND: case PICOSPEC_CALL_VERIFY_SAMPLE:
+            return seg_table_bytes(dtype, rows, V);
+        default:
+            return 0;                           // every other kernel keeps its intermediate state in LDS
+    }
 }
 
 int64_t picospec_max_load_byte(int which_call, int dtype, int32_t V, int32_t misalign_bytes)
@@ -392,7 +430,7 @@ const char* picospec_strerror(int code)
     switch (code) {
         case PICOSPEC_OK: return "ok";
         case PICOSPEC_EINVAL: return "invalid argument (null pointer, size out of range, temperature <= 0, misaligned base)";
-        case PICOSPEC_EWORKSPACE: return "workspace missing or smaller than picospec_workspace_bytes()";
+        case PICOSPEC_EWORKSPACE: return "workspace smaller than picospec_workspace_bytes() or not on a 16-byte boundary";
         case PICOSPEC_EDTYPE: return "dtype must be PICOSPEC_F32 or PICOSPEC_BF16";
         case PICOSPEC_EHIP: return "HIP runtime call failed";
         case PICOSPEC_EUNSUPPORTED: return "k or V exceeds picospec_limit()";

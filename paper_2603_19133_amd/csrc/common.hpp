@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace picospec {
 
 constexpr int kWave = 64;
@@ -70,6 +72,27 @@ __device__ __forceinline__ T wave_sum(T v) {
     v += dpp<kDppRowHalfMirror>(v);
     v += dpp<kDppRowMirror>(v);
     return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
+}
+
+// sum over the 64 lanes, valid in lane 63 only: four shift-and-add steps inside each row of 16 lanes, then the rows'
+// totals handed on to the rows behind them (six instructions, none of them reads a lane into a scalar)
+__device__ __forceinline__ float wave_sum_last(float v) {
+    auto step = [](float x, auto ctrl, auto row_mask) {
+        int w;
+        __builtin_memcpy(&w, &x, 4);
+        w = __builtin_amdgcn_update_dpp(0, w, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, true);
+        float y;
+        __builtin_memcpy(&y, &w, 4);
+        return y;
+    };
+    using all = std::integral_constant<int, 0xF>;
+    v += step(v, std::integral_constant<int, kDppRowShr + 1>{}, all{});
+    v += step(v, std::integral_constant<int, kDppRowShr + 2>{}, all{});
+    v += step(v, std::integral_constant<int, kDppRowShr + 4>{}, all{});
+    v += step(v, std::integral_constant<int, kDppRowShr + 8>{}, all{});
+    v += step(v, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});   // row_bcast:15 into rows 1 and 3
+    v += step(v, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});   // row_bcast:31 into rows 2 and 3
+    return v;
 }
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -333,6 +356,112 @@ __device__ __forceinline__ void row_stats_row(
     }
     float M; double S;
     block_softmax_stats<THREADS / kWave>(os.m, os.s, c, red, M, S);
+    if (tid == 0) {
+        row_max[row] = M;
+        row_sum[row] = (float)S;
+        if (row_lse) row_lse[row] = (float)((double)M * (double)inv_T + log(S));
+    }
+}
+
+// The same statistics, and besides them the row's exponential sums segment by segment (what lets the residual draw
+// locate its token without a second pass over the row).  A wave owns NV * 64 consecutive vectors per trip, one
+// segment; segment `it * WAVES + wave` of the row gets (t, r): the sum over its elements of 2^(z c - r), c = log2(e) / T,
+// with r an integer-valued reference exponent that is the same for the whole wave (every lane adds against it, so the
+// trip's sum is one wave-wide addition; it moves up, and the lanes' running sums are rescaled, only when an element
+// lies more than 2^64 above it: the check is one compare per trip).  Row layout of the table: seg[row * seg_stride + s].
+template <bool BF16, int NV, int THREADS>
+__device__ __forceinline__ void row_stats_seg_row(
+    const int64_t row, const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+    float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse,
+    float2* __restrict__ seg, int seg_stride)
+{
+    constexpr int WAVES = THREADS / kWave;
+    __shared__ double red[2 * WAVES];
+    // the row's table is gathered in LDS and written once, in whole lines, at the end of the row
+    constexpr int kSegLds = 1040;                // segments of the longest row (2^20 elements)
+    __shared__ float2 seg_lds[kSegLds];
+    constexpr int N = Vec<BF16>::N, E = NV * N, TILE_VECS = THREADS * NV;
+    static_assert(E <= 32, "one bit of the validity mask per element");
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const RowView rv = row_view<BF16>(logits, ld, row, V);
+    const int nq = (rv.L + N - 1) / N;
+    const int n_tiles = (nq + TILE_VECS - 1) / TILE_VECS;
+    const float c = 1.4426950408889634f * inv_T;
+    float2* const seg_row = seg + row * (int64_t)seg_stride;
+
+    uint4 cur[NV], nxt[NV];
+    // vector j of this lane in trip `it`: it * TILE_VECS + wave * (NV * 64) + j * 64 + lane
+    const int q_lane = wave * (NV * kWave) + lane;
+    auto load_tile = [&](int it, uint4 (&dst)[NV]) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int q = it * TILE_VECS + q_lane + j * kWave;
+            dst[j] = make_uint4(0, 0, 0, 0);
+            if (vec_in_row<BF16>(rv, q)) dst[j] = load16_stream(rv.base + q);
+        }
+    };
+    load_tile(0, cur);
+    float mx = kNegInf;          // this lane's largest value
+    float r_w = kNegInf;         // the wave's reference exponent (uniform)
+    float s = 0.f;               // this lane's sum of 2^(z c - r_w)
+    for (int it = 0; it < n_tiles; ++it) {
+        if (it + 1 < n_tiles) load_tile(it + 1, nxt);
+        float v[E];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float t[N];
+            unpack<BF16>(cur[j], t);
+#pragma unroll
+            for (int e = 0; e < N; ++e) v[j * N + e] = t[e];
+        }
+        if (it == 0 || it == n_tiles - 1) {
+            unsigned vm = 0;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) vm |= vec_valid_mask<BF16>(rv, it * TILE_VECS + q_lane + j * kWave) << (j * N);
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[e] = (vm >> e) & 1u ? v[e] : kNegInf;
+        }
+        float bm = v[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) bm = fmaxf(bm, v[e]);
+        mx = fmaxf(mx, bm);
+        if (__ballot(bm * c > r_w + 64.f)) {                     // (uniform; the first trip, and outliers)
+            const float rn = ceilf(wave_max(bm) * c);
+            if (rn > r_w) { s *= __builtin_amdgcn_exp2f(r_w - rn); r_w = rn; }   // r_w = -inf: s is 0 and stays 0
+        }
+        const float nr = r_w == kNegInf ? 0.f : -r_w;           // waves that have seen only -inf so far
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc += __builtin_amdgcn_exp2f(fmaf(v[e], c, nr));
+        s += acc;
+        const float t = wave_sum_last(acc);
+        if (lane == kWave - 1 && it * WAVES + wave < kSegLds) seg_lds[it * WAVES + wave] = make_float2(t, r_w);   // (r_w = -inf with t = 0: the reader skips it)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+    }
+    // M = max over the block; S = sum of s 2^(r_w - M c), combined in fp64
+    const float wm = wave_max(mx);
+    if (lane == 0) red[wave] = (double)wm;
+    __syncthreads();
+    {   // (non-temporal stores: ordinary ones, which allocate their lines in the L2, cost this pass 5 % of its bandwidth)
+        typedef float f32x2_t __attribute__((ext_vector_type(2)));
+        for (int sg = tid; sg < min(n_tiles * WAVES, min(seg_stride, kSegLds)); sg += THREADS) {
+            const float2 e = seg_lds[sg];
+            const f32x2_t ev = {e.x, e.y};
+            __builtin_nontemporal_store(ev, reinterpret_cast<f32x2_t*>(&seg_row[sg]));
+        }
+    }
+    float M = kNegInf;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, (float)red[w]);
+    const double mine = r_w == kNegInf ? 0.0 : (double)s * exp2_split((double)r_w - (double)M * (double)c);
+    const double ws = wave_sum(mine);
+    if (lane == 0) red[WAVES + wave] = ws;
+    __syncthreads();
+    double S = 0.0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) S += red[WAVES + w];
     if (tid == 0) {
         row_max[row] = M;
         row_sum[row] = (float)S;

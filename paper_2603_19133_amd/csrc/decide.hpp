@@ -409,6 +409,258 @@ __device__ __forceinline__ void residual_sequence(
     }
 }
 
+// ---------------------------------------------------------------- the same draw from the row's segment table
+//
+// With the exponential sums of the target row's segments at hand (written by the statistics pass: row_stats_seg_row)
+// the row is not streamed again.  R = sum_x max(0, P(x) - qhat(x)) = sum over segments of (P(segment) - T(segment)),
+// T = sum over the record's entries in the segment of min(P(x), qhat(x)): one gathered logit per record entry.  The
+// segment in which the cumulative residual crosses u R is then read (one to four KB) and the token named as before.
+// T is summed in 2^-62 fixed point (integer LDS atomics: the order of the additions does not change the result).
+
+constexpr int kMaxSegTable = 1040;                               // segments of the longest row (2^20 elements: 1025 of 4 KB or of 2 KB)
+constexpr int kMaxSegElems = 256 * 8;                            // elements of the largest segment (256 vectors of bf16)
+
+struct __align__(16) SegResidualShared {
+    double pseg[kMaxSegTable];                 // P of each segment, then its residual mass
+    unsigned long long tfix[kMaxSegTable];     // T of each segment, 2^-62 fixed point
+    float qimg[kMaxSegElems];                  // qhat image of the chosen segment
+    double red[2 * kWaves];
+    double before;
+    int seg_pick, seg_last;
+};
+
+template <bool BF16>
+__device__ __forceinline__ void residual_seg_sequence(
+    const int b, const int j_in, const void* __restrict__ tgt_logits, int64_t ld, int V, float inv_T,
+    const int32_t* __restrict__ seq_off, const float* __restrict__ tgt_max, const SegHeader* __restrict__ table,
+    const int seg_vecs, const int stride,
+    const int32_t* __restrict__ q_idx, const float* __restrict__ q_prob,
+    const int32_t* __restrict__ q_count, const float* __restrict__ q_mass, int k, int renorm,
+    const float* __restrict__ uniforms,
+    int32_t* __restrict__ out_tok, float* __restrict__ resid_mass, uint32_t* __restrict__ flags)
+{
+    __shared__ SegResidualShared sh;
+    constexpr int N = Vec<BF16>::N;
+    constexpr int SP = kMaxK / kThreads;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int d0 = seq_off[b];
+    int g = seq_off[b + 1] - d0;
+    unsigned fl = 0;
+    if (g < 0) { fl |= 8u; g = 0; }
+    int j = j_in;
+    if (j < 0 || j > g) { fl |= 8u; j = j < 0 ? 0 : g; }
+    const int64_t rt = (int64_t)d0 + b + j;
+    const int64_t rd = (int64_t)d0 + j;
+    bool has_q = j < g;
+    const RowView rv = row_view<BF16>(tgt_logits, ld, rt, V);
+    const int nq = (rv.L + N - 1) / N;
+    const int seg_elems = seg_vecs * N;
+    const int n_seg = (nq + seg_vecs - 1) / seg_vecs;
+    const float2* seg_row = reinterpret_cast<const float2*>(table + 1) + rt * (int64_t)stride;
+    // Everything that depends only on the two rows is asked for at once (one trip to memory): the table's header
+    // (checked below), the target row's maximum, the record's count and mass, this thread's entries of the record and
+    // its entries of the segment table.
+    const SegHeader hd = *table;
+    const float M = tgt_max[rt];
+    int cnt = 0;
+    float mass_d = 1.f;
+    int my_id[SP];
+    float my_p[SP];
+    if (has_q) {
+        cnt = q_count[rd];
+        if (renorm) mass_d = q_mass[rd];
+#pragma unroll
+        for (int z = 0; z < SP; ++z) {
+            const int sl = z * kThreads + tid;
+            my_id[z] = -1;
+            my_p[z] = 0.f;
+            if (sl < k) { my_id[z] = q_idx[rd * k + sl]; my_p[z] = q_prob[rd * k + sl]; }
+        }
+        cnt = cnt < 0 ? 0 : (cnt > k ? k : cnt);
+    } else {
+#pragma unroll
+        for (int z = 0; z < SP; ++z) { my_id[z] = -1; my_p[z] = 0.f; }
+    }
+    const bool table_ok = n_seg <= stride && n_seg <= kMaxSegTable && seg_elems <= kMaxSegElems;
+    float2 my_seg[(kMaxSegTable + kThreads - 1) / kThreads];
+#pragma unroll
+    for (int u = 0; u < (kMaxSegTable + kThreads - 1) / kThreads; ++u) {
+        const int sg = u * kThreads + tid;
+        my_seg[u] = make_float2(0.f, 0.f);
+        if (table_ok && sg < n_seg) my_seg[u] = seg_row[sg];
+    }
+    // ... and, one trip later, the target's logit at each of this thread's record entries
+    float my_z[SP];
+#pragma unroll
+    for (int z = 0; z < SP; ++z) {
+        const int sl = z * kThreads + tid;
+        if (!(sl < cnt && my_id[z] >= 0 && my_id[z] < V)) my_id[z] = -1;
+        my_z[z] = my_id[z] >= 0 ? logit_at<BF16>(tgt_logits, ld, rt, my_id[z]) : 0.f;
+    }
+    const float c = 1.4426950408889634f * inv_T;
+    const double cd = 1.4426950408889634 * (double)inv_T;
+    const double q_scale = 1.0 / (double)mass_d;
+    if (!table_ok || hd.magic != kSegMagic || rt >= hd.rows || hd.stride != stride || hd.seg_vecs != seg_vecs) {
+        if (tid == 0) { out_tok[b] = 0; resid_mass[b] = 0.f; flags[b] = fl | 8u; }     // (not the table of these rows)
+        return;
+    }
+
+    // P of every segment, up to the common factor 1 / S
+    double part = 0.0;
+#pragma unroll
+    for (int u = 0; u < (kMaxSegTable + kThreads - 1) / kThreads; ++u) {
+        const int sg = u * kThreads + tid;
+        if (sg < n_seg) {
+            const float2 e = my_seg[u];
+            const double p = e.x > 0.f ? (double)e.x * exp2_split((double)e.y - (double)M * (double)c) : 0.0;
+            sh.pseg[sg] = p;
+            sh.tfix[sg] = 0ull;
+            part += p;
+        }
+    }
+    part = wave_sum(part);
+    if (lane == 0) sh.red[wave] = part;
+    if (tid == 0) { sh.seg_pick = 0x7FFFFFFF; sh.seg_last = -1; sh.before = 0.0; }
+    __syncthreads();
+    double S = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) S += sh.red[w];
+    const double invS = 1.0 / S;
+    __syncthreads();
+
+    // this thread's share of the record: qhat and min(P, qhat) into the segment's T
+    float my_q[SP];
+#pragma unroll
+    for (int z = 0; z < SP; ++z) {
+        my_q[z] = 0.f;
+        if (my_id[z] >= 0) {
+            const double qh = (double)my_p[z] * q_scale;
+            const double p = exp_emit(my_z[z], M, cd) * invS;
+            const double m = p < qh ? p : qh;
+            my_q[z] = (float)qh;
+            atomicAdd(&sh.tfix[(my_id[z] + rv.o) / seg_elems], (unsigned long long)llrint(m * 4611686018427387904.0));
+        }
+    }
+    __syncthreads();
+
+    // residual mass of every segment, the total, and the segment in which the cumulative residual crosses u R
+    const int per = (n_seg + kThreads - 1) / kThreads;        // contiguous segments per thread
+    const int s0 = min(n_seg, tid * per), s1 = min(n_seg, s0 + per);
+    double R = 0.0, mine = 0.0;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        mine = 0.0;
+        for (int s = s0; s < s1; ++s) {
+            double r = sh.pseg[s] * invS;
+            if (has_q) { r -= (double)sh.tfix[s] * (1.0 / 4611686018427387904.0); r = r > 0.0 ? r : 0.0; }
+            mine += r;
+        }
+        const double tot = wave_sum(mine);
+        __syncthreads();
+        if (lane == 0) sh.red[wave] = tot;
+        __syncthreads();
+        R = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) R += sh.red[w];
+        if (R > 0.0 || !has_q) break;
+        fl |= 4u;                                              // P == qhat numerically: draw from P itself
+        has_q = false;
+    }
+    auto seg_mass = [&](int s) {
+        double r = sh.pseg[s] * invS;
+        if (has_q) { r -= (double)sh.tfix[s] * (1.0 / 4611686018427387904.0); r = r > 0.0 ? r : 0.0; }
+        return r;
+    };
+    const double target = (double)uniforms[(int64_t)d0 + b + g] * R;
+    const double incl = wave_scan_incl(mine);
+    __syncthreads();
+    if (lane == kWave - 1) sh.red[kWaves + wave] = incl;
+    __syncthreads();
+    double cum = incl - mine;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) if (w < wave) cum += sh.red[kWaves + w];
+    int my_pick = 0x7FFFFFFF, my_last = -1;
+    for (int s = s0; s < s1; ++s) {
+        const double v = seg_mass(s);
+        if (v > 0.0) my_last = s;
+        if (my_pick == 0x7FFFFFFF && cum + v > target) my_pick = s;
+        if (my_pick == 0x7FFFFFFF) cum += v;
+    }
+    if (my_pick != 0x7FFFFFFF) atomicMin(&sh.seg_pick, my_pick);
+    if (my_last >= 0) atomicMax(&sh.seg_last, my_last);
+    __syncthreads();
+    int pick = sh.seg_pick;
+    const bool crossed = pick != 0x7FFFFFFF;
+    if (!crossed) pick = max(sh.seg_last, 0);                 // rounding: last segment with mass
+    if (crossed && my_pick == pick) sh.before = cum;          // exactly one thread owns the chosen segment
+    const int seg_vec = pick * seg_vecs;                      // first vector of the segment
+    const int seg_lo = seg_vec * N - rv.o;                    // id of its first element
+    for (int i = tid; i < seg_elems; i += kThreads) sh.qimg[i] = 0.f;
+    __syncthreads();
+    if (has_q) {
+#pragma unroll
+        for (int z = 0; z < SP; ++z) {
+            const int off = my_id[z] - seg_lo;
+            if (my_id[z] >= 0 && off >= 0 && off < seg_elems) sh.qimg[off] = my_q[z];
+        }
+    }
+    __syncthreads();
+
+    // read that one segment and name the token (wave 0): ids ascend with (jv, lane, element)
+    if (wave == 0) {
+        const double kappa = -(double)M * cd - log2(S);
+        double base = sh.before;
+        int tok = -1, last_tok = -1;
+        for (int jv = 0; jv * kWave < seg_vecs; ++jv) {
+            const int ql = jv * kWave + lane, q = seg_vec + ql;
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (vec_in_row<BF16>(rv, q)) raw = load16_stream(rv.base + q);
+            float v[N];
+            unpack<BF16>(raw, v);
+            const unsigned vm = vec_valid_mask<BF16>(rv, q);
+            double r[N], sum = 0.0;
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                const double d = exp2_split((double)v[e] * cd + kappa) - (double)sh.qimg[ql * N + e];
+                r[e] = ((vm >> e) & 1u) && d > 0.0 ? d : 0.0;
+                sum += r[e];
+            }
+            const double inc = wave_scan_incl(sum);
+            const unsigned long long hit = (crossed && tok < 0) ? __ballot(base + inc > target) : 0ull;
+            if (hit) {
+                const int owner = __ffsll((long long)hit) - 1;
+                int t = -1;
+                if (lane == owner) {
+                    double cu = base + inc - sum;
+#pragma unroll
+                    for (int e = 0; e < N; ++e) {
+                        cu += r[e];
+                        if (t < 0 && cu > target) t = seg_lo + ql * N + e;
+                    }
+                    if (t < 0) t = seg_lo + ql * N + N - 1;
+                }
+                tok = __shfl(t, owner, kWave);
+            }
+            const unsigned long long any = __ballot(sum > 0.0);   // rounding fallback: the last id of the segment with mass
+            if (any) {
+                const int owner = 63 - __clzll((long long)any);
+                int t = -1;
+                if (lane == owner) {
+#pragma unroll
+                    for (int e = 0; e < N; ++e) if (r[e] > 0.0) t = seg_lo + ql * N + e;
+                }
+                last_tok = __shfl(t, owner, kWave);
+            }
+            base += __shfl(inc, kWave - 1, kWave);
+        }
+        if (tok < 0) tok = last_tok >= 0 ? last_tok : min(max(seg_lo, 0), V - 1);
+        if (lane == 0) {
+            out_tok[b] = tok;
+            resid_mass[b] = (fl & 4u) ? 0.f : (float)R;
+            flags[b] = fl;
+        }
+    }
+}
+
 }  // namespace
 
 }  // namespace picospec

@@ -71,8 +71,33 @@ hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int3
                                int k, int n_rows, const float* uniforms, int32_t* tok, float* q_scalar,
                                hipStream_t stream);
 
+// Launch shape of the row statistics (threads per row, 16-byte vectors per thread and trip) for a dtype and a row
+// count, and with it the layout of the optional segment table: a segment is what one wave reads per trip, seg_vecs
+// consecutive vectors; a row owns `stride` entries (float2: sum, reference exponent).
+struct StatsShape { int threads, nv, seg_vecs, stride; };
+inline StatsShape stats_shape(int dtype, int64_t n_rows, int V) {
+    StatsShape sh;
+    if (dtype != 1)            { sh.threads = 1024; sh.nv = 4; }   // fp32 rows are HBM-bound with any shape
+    else if (n_rows >= 2048)   { sh.threads = 256;  sh.nv = 4; }   // bf16: twice the arithmetic per byte; small workgroups,
+    else if (n_rows >= 1024)   { sh.threads = 512;  sh.nv = 2; }   // many per CU, keep the vector ALUs busier as long as
+    else                       { sh.threads = 1024; sh.nv = 2; }   // there are rows enough to fill the chip with them
+    const int esz = dtype == 1 ? 2 : 4;
+    const int64_t nq_max = ((int64_t)V * esz + 15) / 16 + 1;       // (a row off the 16-byte boundary spans one vector more)
+    const int tile_vecs = sh.threads * sh.nv;
+    sh.seg_vecs = 64 * sh.nv;
+    sh.stride = (int)((nq_max + tile_vecs - 1) / tile_vecs) * (sh.threads / 64);
+    return sh;
+}
+// bytes of the segment table of `rows` rows (16-byte header in front: see SegHeader)
+struct SegHeader { int32_t magic, seg_vecs, stride, rows; };
+constexpr int32_t kSegMagic = 0x53454731;
+inline size_t seg_table_bytes(int dtype, int64_t rows, int V) {
+    return sizeof(SegHeader) + (size_t)rows * (size_t)stats_shape(dtype, rows, V).stride * 8;
+}
+
+// seg (nullable): the segment table, seg_stride entries per row
 hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
-                            float* row_max, float* row_sum, float* row_lse, hipStream_t stream);
+                            float* row_max, float* row_sum, float* row_lse, void* seg_table, hipStream_t stream);
 
 // the same for the target rows pos_begin[b]..pos_end[b] of every sequence only (nullable: 0 / gamma_b)
 hipError_t launch_row_stats_range(const void* logits, int dtype, int64_t ld, int V, float temperature, int B,
@@ -93,15 +118,16 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            const float* tgt_max, const float* tgt_sum,
                            const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                            int k, int renorm, const float* uniforms,
-                           int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream);
+                           int32_t* out_tok, float* resid_mass, uint32_t* flags, const void* seg_table, int64_t n_rows, hipStream_t stream);
 
-// acceptance and residual draw of every sequence in one launch (small rounds)
+// acceptance and residual draw of every sequence in one launch; seg_table (nullable, also in launch_residual): the
+// table of the n_rows target rows from launch_row_stats, with which the draw does not stream its row again
 hipError_t launch_decide(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
                          int B, const int32_t* seq_off, const int32_t* draft_tok,
                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                          int k, int renorm, const float* uniforms, const float* tgt_max, const float* tgt_sum,
                          int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
-                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, hipStream_t stream);
+                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, const void* seg_table, int64_t n_rows, hipStream_t stream);
 
 hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t ld, int V, float temperature,
                                   int B, const int32_t* seq_off, const int32_t* n_accept,

@@ -49,6 +49,39 @@ __global__ __launch_bounds__(kThreads) void decide_kernel(
                             q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass, res_flags);
 }
 
+// The same two kernels with the target rows' segment table at hand (no second pass over a row).
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void residual_seg_kernel(
+    const void* __restrict__ tgt_logits, int64_t ld, int V, float inv_T,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ n_accept,
+    const float* __restrict__ tgt_max, const SegHeader* __restrict__ table, int seg_vecs, int stride,
+    const int32_t* __restrict__ q_idx, const float* __restrict__ q_prob,
+    const int32_t* __restrict__ q_count, const float* __restrict__ q_mass, int k, int renorm,
+    const float* __restrict__ uniforms,
+    int32_t* __restrict__ out_tok, float* __restrict__ resid_mass, uint32_t* __restrict__ flags)
+{
+    residual_seg_sequence<BF16>(blockIdx.x, n_accept[blockIdx.x], tgt_logits, ld, V, inv_T, seq_off, tgt_max, table, seg_vecs, stride,
+                                q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass, flags);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void decide_seg_kernel(
+    const void* __restrict__ tgt_logits, int64_t ld, int V, float inv_T,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ draft_tok,
+    const int32_t* __restrict__ q_idx, const float* __restrict__ q_prob,
+    const int32_t* __restrict__ q_count, const float* __restrict__ q_mass, int k, int renorm,
+    const float* __restrict__ uniforms, const float* __restrict__ tgt_max, const float* __restrict__ tgt_sum,
+    const SegHeader* __restrict__ table, int seg_vecs, int stride,
+    int32_t* __restrict__ n_accept, float* __restrict__ p_tok, float* __restrict__ q_tok, uint32_t* __restrict__ flags,
+    int32_t* __restrict__ out_tok, float* __restrict__ resid_mass, uint32_t* __restrict__ res_flags)
+{
+    const int first = accept_sequence<BF16>(blockIdx.x, tgt_logits, ld, V, inv_T, seq_off, draft_tok, q_idx, q_prob,
+                                            q_count, q_mass, k, renorm, nullptr, uniforms, tgt_max, tgt_sum,
+                                            n_accept, p_tok, q_tok, flags, nullptr, nullptr);
+    residual_seg_sequence<BF16>(blockIdx.x, first, tgt_logits, ld, V, inv_T, seq_off, tgt_max, table, seg_vecs, stride,
+                                q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass, res_flags);
+}
+
 }  // namespace
 
 hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
@@ -56,8 +89,16 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            const float* tgt_max, const float* tgt_sum,
                            const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                            int k, int renorm, const float* uniforms,
-                           int32_t* out_tok, float* resid_mass, uint32_t* flags, hipStream_t stream)
+                           int32_t* out_tok, float* resid_mass, uint32_t* flags, const void* seg_table, int64_t n_rows, hipStream_t stream)
 {
+    if (seg_table) {
+        if (B == 0) return hipSuccess;
+        const float it = 1.0f / temperature;
+        const StatsShape sh = stats_shape(dtype, n_rows, V);
+        if (dtype == 1) hipLaunchKernelGGL(residual_seg_kernel<true>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, it, seq_off, n_accept, tgt_max, (const SegHeader*)seg_table, sh.seg_vecs, sh.stride, q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass, flags);
+        else            hipLaunchKernelGGL(residual_seg_kernel<false>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, it, seq_off, n_accept, tgt_max, (const SegHeader*)seg_table, sh.seg_vecs, sh.stride, q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, out_tok, resid_mass, flags);
+        return hipGetLastError();
+    }
     static DeviceFlags limit_raised[2] = {};
     const size_t smem = sizeof(ResidualShared);
     auto f32 = residual_kernel<false>;
@@ -80,8 +121,16 @@ hipError_t launch_decide(const void* tgt_logits, int dtype, int64_t ld, int V, f
                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                          int k, int renorm, const float* uniforms, const float* tgt_max, const float* tgt_sum,
                          int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
-                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, hipStream_t stream)
+                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, const void* seg_table, int64_t n_rows, hipStream_t stream)
 {
+    if (seg_table) {
+        if (B == 0) return hipSuccess;
+        const float it = 1.0f / temperature;
+        const StatsShape sh = stats_shape(dtype, n_rows, V);
+        if (dtype == 1) hipLaunchKernelGGL(decide_seg_kernel<true>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, it, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, (const SegHeader*)seg_table, sh.seg_vecs, sh.stride, n_accept, p_tok, q_tok, flags, out_tok, resid_mass, res_flags);
+        else            hipLaunchKernelGGL(decide_seg_kernel<false>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, it, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, (const SegHeader*)seg_table, sh.seg_vecs, sh.stride, n_accept, p_tok, q_tok, flags, out_tok, resid_mass, res_flags);
+        return hipGetLastError();
+    }
     static DeviceFlags limit_raised[2] = {};
     const size_t smem = sizeof(ResidualShared);
     auto f32 = decide_kernel<false>;

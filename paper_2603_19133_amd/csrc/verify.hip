@@ -17,6 +17,18 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(
     row_stats_row<BF16, NV, THREADS>(blockIdx.x, logits, ld, V, inv_T, row_max, row_sum, row_lse);
 }
 
+// The statistics together with the row's segment table (row_stats_seg_row); workgroup 0 also writes the table's header.
+template <bool BF16, int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void row_stats_seg_kernel(
+    const void* __restrict__ logits, int64_t ld, int V, float inv_T,
+    float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse,
+    SegHeader* __restrict__ header, int seg_stride)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *header = SegHeader{kSegMagic, NV * kWave, seg_stride, (int32_t)gridDim.x};
+    row_stats_seg_row<BF16, NV, THREADS>(blockIdx.x, logits, ld, V, inv_T, row_max, row_sum, row_lse,
+                                         reinterpret_cast<float2*>(header + 1), seg_stride);
+}
+
 // The same for the target rows begin_b..end_b of every sequence only (verification of a part of the
 // draft): workgroup (t, b) of a (gamma_max + 1) x B grid takes position t of sequence b or leaves.
 template <bool BF16, int NV, int THREADS>
@@ -73,19 +85,18 @@ hipError_t launch_row_stats_range(const void* logits, int dtype, int64_t ld, int
 }
 
 hipError_t launch_row_stats(const void* logits, int dtype, int64_t ld, int n_rows, int V, float temperature,
-                            float* row_max, float* row_sum, float* row_lse, hipStream_t stream)
+                            float* row_max, float* row_sum, float* row_lse, void* seg_table, hipStream_t stream)
 {
     if (n_rows == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
-    // fp32 rows are HBM-bound with any shape.  bf16 rows carry twice the arithmetic per byte: small
-    // workgroups (many per CU, out of step, short ragged tails) keep the vector ALUs busier, as long as
-    // there are enough rows to fill the chip with them.
+    const StatsShape sh = stats_shape(dtype, n_rows, V);
 #define PICOSPEC_ROW_STATS(BF, NVV, TH) \
-    hipLaunchKernelGGL((row_stats_kernel<BF, NVV, TH>), dim3(n_rows), dim3(TH), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse)
-    if (dtype != 1)           PICOSPEC_ROW_STATS(false, 4, kThreads);
-    else if (n_rows >= 2048)  PICOSPEC_ROW_STATS(true, 4, 256);
-    else if (n_rows >= 1024)  PICOSPEC_ROW_STATS(true, 2, 512);
-    else                      PICOSPEC_ROW_STATS(true, 2, kThreads);
+    do { if (seg_table) hipLaunchKernelGGL((row_stats_seg_kernel<BF, NVV, TH>), dim3(n_rows), dim3(TH), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse, (SegHeader*)seg_table, sh.stride); \
+         else hipLaunchKernelGGL((row_stats_kernel<BF, NVV, TH>), dim3(n_rows), dim3(TH), 0, stream, logits, ld, V, inv_T, row_max, row_sum, row_lse); } while (0)
+    if (dtype != 1)              PICOSPEC_ROW_STATS(false, 4, kThreads);
+    else if (sh.threads == 256)  PICOSPEC_ROW_STATS(true, 4, 256);
+    else if (sh.threads == 512)  PICOSPEC_ROW_STATS(true, 2, 512);
+    else                         PICOSPEC_ROW_STATS(true, 2, kThreads);
 #undef PICOSPEC_ROW_STATS
     return hipGetLastError();
 }

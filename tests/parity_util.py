@@ -74,8 +74,9 @@ class GpuRound:
     res: ps.Residual
 
 
-def gpu_round(r: W.Round, tok: np.ndarray, device, renorm: int = 1) -> GpuRound:
-    """The library's three calls on the same inputs; the drafted tokens are the oracle's."""
+def gpu_round(r: W.Round, tok: np.ndarray, device, renorm: int = 1, seg: bool = False) -> GpuRound:
+    """The library's three calls on the same inputs; the drafted tokens are the oracle's.  seg: with the optional
+    workspace, i.e. verify leaves the target rows' segment table and the draw works from it."""
     w = r.workload
     draft = to_device(r.draft_logits, device)
     tgt = to_device(r.tgt_logits, device)
@@ -83,8 +84,9 @@ def gpu_round(r: W.Round, tok: np.ndarray, device, renorm: int = 1) -> GpuRound:
     uni = torch.from_numpy(r.uniforms).to(device)
     dtok = torch.from_numpy(tok).to(device)
     q = ps.compress(draft, w.V, w.T, w.k, w.top_p)
-    ver = ps.verify(tgt, w.V, w.T, seq_off, r.N, dtok, q, uni, renorm=renorm)
-    res = ps.sample_residual(tgt, w.V, w.T, seq_off, r.N, ver, q, uni, renorm=renorm)
+    ws = ps.alloc_workspace(tgt.dtype, r.N + r.B, w.V, device) if seg else None
+    ver = ps.verify(tgt, w.V, w.T, seq_off, r.N, dtok, q, uni, renorm=renorm, workspace=ws)
+    res = ps.sample_residual(tgt, w.V, w.T, seq_off, r.N, ver, q, uni, renorm=renorm, workspace=ws)
     torch.cuda.synchronize()
     return GpuRound(q, ver, res)
 

@@ -38,17 +38,18 @@ WORKLOAD_CASES = [
 ]
 
 
+@pytest.mark.parametrize("seg", [False, True])       # without / with the segment table of the target rows
 @pytest.mark.parametrize("name,scale,rnd", WORKLOAD_CASES)
-def test_round_matches_oracle(gpu, pu, name, scale, rnd):
+def test_round_matches_oracle(gpu, pu, name, scale, rnd, seg):
     w = W.WORKLOADS[name]
     if scale:
         w = w.scaled(**scale)
     _announce("round", name, scale, "round", rnd, "V", w.V, "k", w.k, w.dtype)
     r = W.build_round(w, rnd)
     o = pu.oracle_round(r)
-    g = pu.gpu_round(r, o.tok, gpu)
+    g = pu.gpu_round(r, o.tok, gpu, seg=seg)
     st = pu.compare_round(g, o, r)
-    print("[stats]", name, {k: v for k, v in st.items() if k != "topp_excluded"}, flush=True)
+    print("[stats]", name, "seg" if seg else "", {k: v for k, v in st.items() if k != "topp_excluded"}, flush=True)
     if name in ("cfg1", "cfg2", "cfg3"):
         assert st["mismatch_accept"] == 0 and st["mismatch_draw"] == 0
 
@@ -317,8 +318,9 @@ def test_ragged_small_rounds(gpu, pu, renorm, dtype):
         w = W.Workload("ragged", 91, B, 0, 6, V, dtype, 0.8, k, 0.0, 1, "custom")
         r = _custom_round(w, draft, tgt, off, rng.random(N + B, dtype=np.float32), rng.random(N, dtype=np.float32))
         o = pu.oracle_round(r, renorm=renorm)
-        gq = pu.gpu_round(r, o.tok, gpu, renorm=renorm)
-        st = pu.compare_round(gq, o, r, max_excluded_frac=0.05)
+        for seg in (False, True):
+            gq = pu.gpu_round(r, o.tok, gpu, renorm=renorm, seg=seg)
+            st = pu.compare_round(gq, o, r, max_excluded_frac=0.05)
         assert 0 < o.ver.n_accept.sum() < N
 
 
@@ -343,8 +345,9 @@ def test_round_at_the_largest_vocabulary_and_record(gpu, pu, ps, dtype):
     w = W.Workload("largest", 92, B, 0, 2, V, dtype, 1.1, k, 0.0, 1, "custom")
     r = _custom_round(w, draft, tgt, off, rng.random(N + B, dtype=np.float32), rng.random(N, dtype=np.float32))
     o = pu.oracle_round(r)
-    gq = pu.gpu_round(r, o.tok, gpu)
-    pu.compare_round(gq, o, r, max_excluded_frac=0.34)
+    for seg in (False, True):
+        gq = pu.gpu_round(r, o.tok, gpu, seg=seg)
+        pu.compare_round(gq, o, r, max_excluded_frac=0.34)
     orec = oracle.compress_rejected(r.tgt_logits, V, w.T, r.seq_off, o.ver.n_accept, k)
     grec = ps.compress_rejected(pu.to_device(r.tgt_logits, gpu), V, w.T, torch.from_numpy(r.seq_off).to(gpu), N,
                                 torch.from_numpy(o.ver.n_accept).to(gpu), k)
@@ -380,9 +383,10 @@ def test_round_at_extreme_temperatures(gpu, pu, T, spread, dtype):
     w = W.Workload("extreme", 93, B, 0, 5, V, dtype, T, k, 0.0, 1, "custom")
     r = _custom_round(w, draft, tgt, off, rng.random(N + B, dtype=np.float32), rng.random(N, dtype=np.float32))
     o = pu.oracle_round(r)
-    gq = pu.gpu_round(r, o.tok, gpu)
-    # (peaked by construction: sequences whose oracle residual mass lies below PEAKED_R carry the absolute term)
-    pu.compare_round(gq, o, r, max_excluded_frac=0.34, strict=False)
+    for seg in (False, True):
+        gq = pu.gpu_round(r, o.tok, gpu, seg=seg)
+        # (peaked by construction: sequences whose oracle residual mass lies below PEAKED_R carry the absolute term)
+        pu.compare_round(gq, o, r, max_excluded_frac=0.34, strict=False)
 
 
 def test_scalar_q_uplink_and_foreign_tokens(gpu, pu, ps):
@@ -579,6 +583,13 @@ def test_full_size_round_sampled_sequences(gpu, pu, ps, name, rnd, n_sample):
     g = pu.GpuRound(q, ver, res)
     st = pu.compare_round(pu.slice_gpu_round(g, full, sub), o, sub, max_excluded_frac=0.05)
     print("[stats]", name, rnd, {k: v for k, v in st.items() if k != "topp_excluded"}, flush=True)
+    # the same round through the fused call on the existing records, with the segment table (no second pass over a row)
+    ws = ps.alloc_workspace(tgt.dtype, full.N + full.B, w.V, gpu, ps.CALL_VERIFY_SAMPLE)
+    ver2, res2 = ps.verify_sample(tgt, w.V, w.T, seq_off, full.N, tok, q, uni, workspace=ws)
+    torch.cuda.synchronize()
+    st2 = pu.compare_round(pu.slice_gpu_round(pu.GpuRound(q, ver2, res2), full, sub), o, sub, max_excluded_frac=0.05)
+    print("[stats]", name, rnd, "verify_sample + segment table", {k: v for k, v in st2.items() if k != "topp_excluded"}, flush=True)
+    assert torch.equal(ver2.n_accept, ver.n_accept) or st2["mismatch_accept"] > 0
     # properties that hold for every row and sequence of the batch
     idx, prob, cnt, mass = pu.n(q.idx), pu.n(q.prob), pu.n(q.count), pu.n(q.mass)
     assert ((cnt >= 1) & (cnt <= w.k)).all()

@@ -129,6 +129,7 @@ def test_round_random_sweep(gpu, block):
         print("[case] round sweep", seed, c, flush=True)
         o = pu.oracle_round(r, renorm=renorm)
         pu.compare_round(pu.gpu_round(r, o.tok, gpu, renorm=renorm), o, r, max_excluded_frac=0.34, strict=False)
+        pu.compare_round(pu.gpu_round(r, o.tok, gpu, renorm=renorm, seg=True), o, r, max_excluded_frac=0.34, strict=False)
         d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
         w = r.workload
         q, ver, res = ps.round(pu.to_device(r.draft_logits, gpu), pu.to_device(r.tgt_logits, gpu), w.V, w.T, d(r.seq_off),

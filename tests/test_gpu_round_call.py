@@ -44,6 +44,18 @@ def test_round_call_matches_oracle_and_separate_calls(gpu, pu, ps, name, scale, 
     torch.cuda.synchronize()
     one = pu.GpuRound(q, ver, res)
     pu.compare_round(one, o, r, max_excluded_frac=0.34)
+    # the same call with the workspace (the draw works from the target rows' segment table), and the fused call on
+    # the existing records, with and without it
+    ws = ps.alloc_workspace(torch.float32 if w.dtype == "f32" else torch.bfloat16, r.N + r.B, w.V, gpu, ps.CALL_ROUND)
+    q3, ver3, res3 = ps.round(pu.to_device(r.draft_logits, gpu), pu.to_device(r.tgt_logits, gpu), w.V, w.T, d(r.seq_off),
+                              r.N, d(o.tok), w.k, d(r.uniforms), top_p=w.top_p, renorm=renorm, workspace=ws)
+    torch.cuda.synchronize()
+    pu.compare_round(pu.GpuRound(q3, ver3, res3), o, r, max_excluded_frac=0.34)
+    for wsp in (None, ws):
+        ver4, res4 = ps.verify_sample(pu.to_device(r.tgt_logits, gpu), w.V, w.T, d(r.seq_off), r.N, d(o.tok), sep.q, d(r.uniforms),
+                                      renorm=renorm, workspace=wsp)
+        torch.cuda.synchronize()
+        pu.compare_round(pu.GpuRound(sep.q, ver4, res4), o, r, max_excluded_frac=0.34)
     # the records come from the same code: bit for bit; the target statistics of the two-launch schedule are summed by
     # 512 threads instead of 1024, so everything behind them agrees to rounding and the decisions wherever the oracle
     # does not call them knife-edge
