@@ -72,7 +72,8 @@ enum {
     PICOSPEC_EWORKSPACE = -2,  /* a workspace was given that is smaller than picospec_workspace_bytes() says, or misaligned */
     PICOSPEC_EDTYPE = -3,      /* dtype is neither PICOSPEC_F32 nor PICOSPEC_BF16 */
     PICOSPEC_EHIP = -4,        /* a HIP runtime call (launch, attribute) failed */
-    PICOSPEC_EUNSUPPORTED = -5 /* k or V beyond the limits reported by picospec_limit() */
+    PICOSPEC_EUNSUPPORTED = -5,/* k or V beyond the limits reported by picospec_limit() */
+    PICOSPEC_ESCRATCH = -6     /* picospec_verify_sample_static: the rows' segment table exceeds the library's fixed array */
 };
 
 /* bits of flags[b] */
@@ -272,6 +273,30 @@ int picospec_verify_sample(const void* tgt_logits, int dtype, int64_t ld, int32_
                            float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* verify_flags,
                            int32_t* out_tok, float* resid_mass, uint32_t* residual_flags,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * picospec_verify_sample for callers that cannot allocate device memory and have none to spare for a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments (without the
+ * workspace), same kernels, same outputs bit for bit as picospec_verify_sample with a workspace; the target rows'
+ * segment table lives in a fixed array of picospec_static_scratch_bytes() bytes (8 MiB) inside the library's device
+ * image, one copy per GPU, held until the process ends.  The call allocates and frees nothing.
+ *   - Sizes: picospec_workspace_bytes(PICOSPEC_CALL_VERIFY_SAMPLE, dtype, n_draft + B, V, k) must not exceed the array
+ *     (about 6,500 target rows at V = 152 K fp32, 13,000 bf16), else PICOSPEC_ESCRATCH and nothing is launched.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different streams, or
+ *     different threads) race on it; calls on one stream are ordered and safe.  The array keeps the last call's table;
+ *     nothing in it has to be cleared (every entry that is read is written first by the same call).
+ *   - The first call on a device asks the runtime for the array's address there (no allocation), with that device current.
+ */
+int picospec_verify_sample_static(const void* tgt_logits, int dtype, int64_t ld, int32_t V, float temperature,
+                                  int32_t B, int32_t n_draft, const int32_t* seq_off, const int32_t* draft_tok,
+                                  const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
+                                  int32_t k, int renorm, const float* uniforms,
+                                  int32_t* n_accept, float* p_tok, float* q_tok,
+                                  float* tgt_max, float* tgt_sum, float* tgt_lse, uint32_t* verify_flags,
+                                  int32_t* out_tok, float* resid_mass, uint32_t* residual_flags, void* stream);
+
+/* host: size of the fixed array behind picospec_verify_sample_static, in bytes. */
+int64_t picospec_static_scratch_bytes(void);
 
 /*
  * ---- Wire messages of a round (Section 3.3) ----------------------------------------------------

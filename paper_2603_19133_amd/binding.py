@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpicospec.so")
 
 F32, BF16 = 0, 1
-OK, EINVAL, EWORKSPACE, EDTYPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+OK, EINVAL, EWORKSPACE, EDTYPE, EHIP, EUNSUPPORTED, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
 FLAG_TOKEN_NOT_IN_SUPPORT, FLAG_NONFINITE, FLAG_RESIDUAL_EMPTY, FLAG_BAD_INPUT = 1, 2, 4, 8
 CALL_COMPRESS, CALL_SAMPLE_DRAFT, CALL_VERIFY, CALL_SAMPLE_RESIDUAL = 0, 1, 2, 3
 CALL_ROUND, CALL_VERIFY_SAMPLE = 6, 7
@@ -24,7 +24,7 @@ LIMIT_MAX_K, LIMIT_MAX_V = 0, 1
 WIRE_FP32, WIRE_FP16, WIRE_BF16 = 0, 1, 2
 WIRE_BAD_HEADER, WIRE_BAD_BATCH, WIRE_CLAMPED, WIRE_TRUNCATED = 1, 2, 4, 8
 
-EXPORTS = ("picospec_round", "picospec_verify_sample", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
+EXPORTS = ("picospec_round", "picospec_verify_sample", "picospec_verify_sample_static", "picospec_static_scratch_bytes", "picospec_compress", "picospec_sample_draft", "picospec_verify", "picospec_verify_range", "picospec_sample_residual",
            "picospec_row_stats", "picospec_compress_rejected", "picospec_resample_sparse",
            "picospec_pack_downlink", "picospec_unpack_downlink", "picospec_pack_uplink", "picospec_unpack_uplink",
            "picospec_downlink_bytes_max", "picospec_uplink_bytes", "picospec_max_load_byte", "picospec_check_device", "picospec_probe_clock",
@@ -48,6 +48,10 @@ lib.picospec_round.argtypes = [_p, _p, C.c_int, _i64, _i64, _i32, _f, _i32, _i32
 lib.picospec_verify_sample.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _i32, C.c_int, _p,
                                        _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_verify_sample.restype = C.c_int
+lib.picospec_verify_sample_static.argtypes = lib.picospec_verify_sample.argtypes[:-3] + [_p]
+lib.picospec_verify_sample_static.restype = C.c_int
+lib.picospec_static_scratch_bytes.argtypes = []
+lib.picospec_static_scratch_bytes.restype = _i64
 lib.picospec_sample_residual.argtypes = [_p, C.c_int, _i64, _i32, _f, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _p,
                                          _i32, C.c_int, _p, _p, _p, _p, _p, _sz, _p]
 lib.picospec_row_stats.argtypes = [_p, C.c_int, _i64, _i32, _i32, _f, _p, _p, _p, _p]
@@ -276,6 +280,23 @@ def alloc_residual(B: int, device) -> Residual:
     return Residual(torch.empty(B, dtype=torch.int32, device=device),
                     torch.empty(B, dtype=torch.float32, device=device),
                     torch.empty(B, dtype=torch.int32, device=device))
+
+
+def verify_sample_static(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,
+                         draft_tok: torch.Tensor, q: "Compressed", uniforms: torch.Tensor, ver: "Verified", res: "Residual",
+                         renorm: int = 1) -> None:
+    """picospec_verify_sample_static into `ver` and `res` (the caller's: this wrapper allocates nothing either)."""
+    dt, ld = _logits_2d(tgt_logits)
+    B = seq_off.shape[0] - 1
+    _check(lib.picospec_verify_sample_static(_ptr(tgt_logits), dt, ld, V, temperature, B, n_draft, _ptr(seq_off), _ptr(draft_tok),
+                                             _ptr(q.idx), _ptr(q.prob), _ptr(q.count), _ptr(q.mass), q.k, renorm, _ptr(uniforms),
+                                             _ptr(ver.n_accept), _ptr(ver.p_tok), _ptr(ver.q_tok),
+                                             _ptr(ver.tgt_max), _ptr(ver.tgt_sum), _ptr(ver.tgt_lse), _ptr(ver.flags),
+                                             _ptr(res.out_tok), _ptr(res.resid_mass), _ptr(res.flags), _stream()))
+
+
+def static_scratch_bytes() -> int:
+    return int(lib.picospec_static_scratch_bytes())
 
 
 def sample_residual(tgt_logits: torch.Tensor, V: int, temperature: float, seq_off: torch.Tensor, n_draft: int,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpicospec.so")
-SOURCES = ["api.hip", "compress.hip", "verify.hip", "residual.hip", "downlink.hip", "wire.hip", "selfcheck.hip"]
+SOURCES = ["api.hip", "compress.hip", "verify.hip", "residual.hip", "downlink.hip", "wire.hip", "selfcheck.hip", "noalloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off (scalar fp32 code only); the compiler's rewrite of
 # same-address LDS atomics into a wave-wide scan is switched off (the compress kernel issues one

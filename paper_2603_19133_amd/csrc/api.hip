@@ -434,6 +434,7 @@ const char* picospec_strerror(int code)
         case PICOSPEC_EDTYPE: return "dtype must be PICOSPEC_F32 or PICOSPEC_BF16";
         case PICOSPEC_EHIP: return "HIP runtime call failed";
         case PICOSPEC_EUNSUPPORTED: return "k or V exceeds picospec_limit()";
+        case PICOSPEC_ESCRATCH: return "the target rows' segment table exceeds the fixed array of picospec_verify_sample_static (picospec_static_scratch_bytes())";
         default: return "unknown picospec error code";
     }
 }
