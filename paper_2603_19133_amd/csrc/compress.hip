@@ -548,6 +548,22 @@ __device__ __forceinline__ void compress_row(
         os.s += acc;
         return bm;
     };
+    // The optimistic pass's form: the reference exponent is fixed for the whole row (set from the sample's largest
+    // value, the same for every thread), so an element costs its exponent, the exponential and an add, and neither
+    // the largest value nor the reference is followed: the row's largest value is the largest candidate, and a row
+    // whose values rise so far above the sample's that the sum could overflow gives the pass up at its end.
+    auto add_sum = [&](auto ee_tag, const float* v, bool edge, float nr) {
+        constexpr int EE = decltype(ee_tag)::value;
+        float acc = 0.f;
+        if (edge) {
+#pragma unroll
+            for (int e = 0; e < EE; ++e) acc += v[e] == v[e] ? __builtin_amdgcn_exp2f(fmaf(v[e], c, nr)) : 0.f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < EE; ++e) acc += __builtin_amdgcn_exp2f(fmaf(v[e], c, nr));
+        }
+        os.s += acc;
+    };
     // Safe pass: appending the elements that pass (v > tau, or with ALL every element that is not NaN)
     // by wave-wide reservation, so that a reservation that does not fit writes nothing and can be
     // repeated after a prune.  reserve_vecs counts the wave's candidates (one ballot per element
@@ -607,13 +623,14 @@ __device__ __forceinline__ void compress_row(
     // that they stay straight-line code (predication by EXEC, no branches for the compiler to lay
     // out): claim_asm forms the lane mask, claims under it and hands the mask on; put_asm waits for
     // the claimed slots and writes under the same masks.  The counter
-    // counts bytes of cand_val (4 per candidate) so that a clamped slot is the LDS address; slots behind
-    // the buffer's end fall onto its last one: once the count has passed the end the pass is lost anyway.
+    // starts at the LDS address of cand_val and counts bytes (4 per candidate), so that a claimed slot, clamped,
+    // is the address to write to; slots behind the buffer's end fall onto its last one: once the count has
+    // passed the end the pass is lost anyway.
     typedef __attribute__((address_space(3))) unsigned lds_u32;
     const unsigned cnt_addr = (unsigned)(uintptr_t)(lds_u32*)&sh.cnt;
     const unsigned val_addr = (unsigned)(uintptr_t)(lds_u32*)&sh.cand_val[0];
-    unsigned four = 4u, wrap = (unsigned)(kCap * 4 - 4);
-    asm volatile("" : "+v"(four), "+v"(wrap));
+    unsigned four = 4u, last_slot = val_addr + (unsigned)(kCap * 4 - 4);
+    asm volatile("" : "+v"(four), "+v"(last_slot));
     auto claim_asm = [&, four](auto ee_tag, const float* v, float tau, int* slot, unsigned long long* passed) {
         constexpr int EE = decltype(ee_tag)::value;
         unsigned ca = cnt_addr;
@@ -630,7 +647,7 @@ __device__ __forceinline__ void compress_row(
                          : "memory", "scc");
         }
     };
-    auto put_asm = [&, wrap](auto nvv_tag, const float* v, int* slot, const unsigned long long* passed, int x0) {
+    auto put_asm = [&, last_slot](auto nvv_tag, const float* v, int* slot, const unsigned long long* passed, int x0) {
         constexpr int NVV = decltype(nvv_tag)::value;
         static_assert(NVV * N == 8 || NVV * N == 16, "the wait names every slot");
         // the claimed slots have arrived (the running sum is named so that the statistics stay in front)
@@ -645,7 +662,6 @@ __device__ __forceinline__ void compress_row(
         }
         // eight columns at a time: their addresses and ids first (every lane, back to back), then only the write
         // under each column's mask
-        const unsigned va = val_addr;
         static_assert((NVV * N) % 8 == 0, "writes go in blocks of eight columns");
 #pragma unroll
         for (int i0 = 0; i0 < NVV * N; i0 += 8) {
@@ -653,7 +669,7 @@ __device__ __forceinline__ void compress_row(
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int i = i0 + u;
-                                at[u] = min((unsigned)slot[i], wrap) + va;
+                                at[u] = min((unsigned)slot[i], last_slot);
                 id[u] = (unsigned)(x0 + (i / N) * kT * N + i % N);
             }
 #pragma unroll
@@ -684,7 +700,7 @@ __device__ __forceinline__ void compress_row(
     for (int attempt = r_opt > 0 ? 0 : 1; attempt < (FAST ? 1 : 2); ++attempt) {
         const bool optimistic = FAST || attempt == 0;
         if (tid == 0) {
-            sh.cnt = 0;
+            sh.cnt = optimistic ? (int)val_addr : 0;      // (the optimistic pass's counter is the LDS address of the next slot)
             sh.overflowed = 0;
             for (int e = 0; e < 3; ++e) { sh.epoch_overflow[e] = 0; sh.epoch_valid[e] = 0x7FFFFFFF; }
         }
@@ -830,7 +846,12 @@ __device__ __forceinline__ void compress_row(
             // ---- the row from its start, optimistic: waves run free; a reservation that does not fit gives the
             //      pass up.  The ring buffers rotate by role (no copies): while one sub-tile is processed
             //      three are in flight; loads behind the row read zero without touching memory (load_sub).
-            const bool applies = !admit_all;     // a sample without a threshold (rows of -inf) leaves the row to the safe pass
+            // a sample without a threshold (rows of -inf), or with +inf in it, leaves the row to the safe pass
+            const float sample_max = __uint_as_float(bits_of_short_key<BF16>(key_hi));
+            const bool applies = !admit_all && sample_max < __builtin_huge_valf();
+            os.r = sample_max > kNegInf ? ceilf(sample_max * c) : 0.f;      // (the reference exponent of add_sum)
+            float nr = -os.r;
+            asm volatile("" : "+v"(nr));
             if (applies) {
 #pragma unroll
                 for (int t = 0; t < T0; ++t) load_sub(RING - T0 + t, rb[t]);
@@ -840,7 +861,7 @@ __device__ __forceinline__ void compress_row(
                     unsigned long long passed[ES];
                     unpack_vecs(sv_t{}, 0, buf, v, false);
                     claim_asm(es_t{}, v, tau, slot, passed);
-                    add_stats(es_t{}, v, false);
+                    add_sum(es_t{}, v, false, nr);
                     put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     load_sub(sub + RING, buf);
                 };
@@ -852,7 +873,7 @@ __device__ __forceinline__ void compress_row(
                         const bool edge = sub + 1 == n_sub;
                         unpack_vecs(sv_t{}, sub * (kT * SV) + tid, buf, v, edge);
                         claim_asm(es_t{}, v, tau, slot, passed);
-                        add_stats(es_t{}, v, edge);
+                        add_sum(es_t{}, v, edge, nr);
                         put_asm(sv_t{}, v, slot, passed, sub * SUB - rv.o + tid * N);
                     }
                 };
@@ -862,7 +883,7 @@ __device__ __forceinline__ void compress_row(
                     unsigned long long passed[ES];
                     unpack_vecs(sv_t{}, tid, rb[T0], v, true);
                     claim_asm(es_t{}, v, tau, slot, passed);
-                    add_stats(es_t{}, v, true);
+                    add_sum(es_t{}, v, true, nr);
                     put_asm(sv_t{}, v, slot, passed, tid * N - rv.o);
                     load_sub(RING, rb[T0]);
                 }
@@ -876,11 +897,21 @@ __device__ __forceinline__ void compress_row(
                 for (int r = 0; r < RING; ++r) ragged(sub + r, rb[(T0 + 1 + r) % RING]);
             }
             __syncthreads();
-            const int held = sh.cnt >> 2;        // (this pass counts bytes of cand_val)
+            const int held = (int)((unsigned)sh.cnt - val_addr) >> 2;   // (this pass's counter is an LDS byte address)
             // (a threshold of -inf: every entry above -inf is held, so fewer than k of them are still the whole answer)
             enough = applies && !sh.overflowed && held <= kCap && (held >= k || (tau == kNegInf && held >= 1));
             n_held = enough ? held : -1;
             fill = enough && held < k;
+            // the row's largest value is its largest candidate (slots behind the last one hold stale values)
+            float cm = kNegInf;
+            if (enough) {
+#pragma unroll
+                for (int j = 0; j < kCap / kT; ++j) {
+                    const float x = __uint_as_float(sh.cand_val[tid + j * kT]);
+                    cm = tid + j * kT < held ? fmaxf(cm, x) : cm;
+                }
+            }
+            os.mx = cm;
             __syncthreads();                     // everyone has read the verdict before the next attempt resets it
         } else {
             // ---- behind the sample, safe: all waves meet after every sub-tile; a full buffer is pruned back to
@@ -945,6 +976,8 @@ __device__ __forceinline__ void compress_row(
             M = kNegInf;
 #pragma unroll
             for (int w = 0; w < kW; ++w) M = fmaxf(M, (float)sh.red[w]);
+            // (optimistic pass: values so far above the sample's that the sums may have overflowed; the same for every thread)
+            if (optimistic && !(M * c - os.r < 100.f)) { enough = false; n_held = -1; fill = false; }
             const double mine = os.r == kNegInf ? 0.0 : (double)os.s * exp2_split((double)os.r - (double)M * (double)c);
             const double ws = wave_sum(mine);
             if (lane == 0) sh.red[kW + wave] = ws;
@@ -955,9 +988,10 @@ __device__ __forceinline__ void compress_row(
             if (tid == kT - 1) {                 // (off the last wave's critical path later on)
                 float it = inv_T;
                 asm volatile("" : "+s"(it));     // widened here: hoisted to the top of the kernel it would hold two registers throughout
-                lse[row] = (float)((double)M * (double)it + log(S));
+                lse[row] = (float)((double)M * (double)it + log(S));     // (rewritten by the pass that follows a pass given up here)
             }
         }
+        if (!enough) continue;
         key_hi = short_key<BF16>(__float_as_uint(M));
         row_done = true;
         break;

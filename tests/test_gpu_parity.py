@@ -78,7 +78,7 @@ def test_compress_sizes_and_tails(gpu, pu, ps, V, k, dtype):
 @pytest.mark.parametrize("pattern", ["ties", "all_equal", "ascending", "descending", "neg_inf", "signed_zero",
                                      "two_values", "sawtooth", "trend_down", "trend_up", "head_hot", "head_cold",
                                      "hot_cluster", "period_of_the_sample", "masked_3pct", "masked_block", "masked_few",
-                                     "masked_half"])
+                                     "masked_half", "spike"])
 # (three rows: the general kernel at two record lengths; 600 rows of a short record on long rows: the variant with three
 #  workgroups per CU, which leaves the rows its optimistic pass cannot take to a second launch of the general kernel)
 @pytest.mark.parametrize("R,k", [(3, 777), (3, 2500), (600, 777)])
@@ -104,6 +104,11 @@ def test_compress_adversarial_rows(gpu, pu, ps, pattern, dtype, R, k):
         z = np.where(rng.random((R, V)) < 0.01, 2.0, -2.0).astype(np.float32)
     elif pattern == "sawtooth":
         z = np.tile((np.arange(V) % 1000).astype(np.float32) * 0.01, (R, 1))
+    elif pattern == "spike":
+        # one value per row far above all others, at an id that the threshold's sample sees in some rows and misses in
+        # most: the optimistic pass sums exponentials against the sample's largest value and must give such a row up
+        z = (rng.standard_normal((R, V)) * 3).astype(np.float32)
+        z[np.arange(R), (np.arange(R) * 6151 + 1234) % V] = 160.0
     elif pattern.startswith("masked"):
         # vocabulary masks (-inf everywhere but on the allowed ids): more allowed ids than k, fewer than k (the record
         # is then filled up with masked ids in ascending order), a block of ids, half of the vocabulary
