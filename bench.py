@@ -115,7 +115,7 @@ def main() -> int:
         x.q = ps.alloc_compressed(r.N, w.k, dev)
         x.ver = ps.alloc_verified(r.B, r.N, dev)
         x.res = ps.alloc_residual(r.B, dev)
-        x.ws = None if args.no_workspace else ps.alloc_workspace(x.tgt.dtype, r.N + r.B, w.V, dev)
+        x.ws = None if args.no_workspace else ps.alloc_workspace(x.tgt.dtype, r.N + r.B, w.V, dev, ps.CALL_ROUND)
         x.ws_bytes = 0 if x.ws is None else x.ws.numel()
         # untimed set-up: the drafter's tokens come from the compressed draft distributions
         ps.compress(x.draft, w.V, w.T, w.k, w.top_p, out=x.q)

@@ -248,6 +248,9 @@ int picospec_resample_sparse(const void* draft_logits, int dtype, int64_t ld, in
  * bandwidth.  Larger rounds keep the two streaming launches of the separate calls (three in all).
  * The records are the same bit for bit in both schedules; the target statistics of the two-launch schedule are
  * summed in another order, so what depends on them agrees with the separate calls to rounding.
+ * workspace (optional): picospec_workspace_bytes(PICOSPEC_CALL_ROUND, ...) bytes; either schedule then leaves the
+ * target rows' segment table there (in a layout of its own: the table of one call of picospec_round serves that call
+ * only) and draws from it without a second pass over the target row.
  */
 int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, int64_t ld_draft, int64_t ld_tgt,
                    int32_t V, float temperature, int32_t B, int32_t n_draft, const int32_t* seq_off,

@@ -163,12 +163,11 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
     // the workgroup).  A round that leaves most of the chip idle is bound by the serial part of each launch, so
     // its two streaming kernels go out as one as well; a round that fills the chip streams faster with each
     // kernel in its own launch shape.
-    const bool small_round = rows + n_draft <= kRoundSmallRows;     // (bound by its launches: two of them, and no use for the table)
-    if (small_round) workspace = nullptr;
+    const bool small_round = rows + n_draft <= kRoundSmallRows;     // (bound by its launches: two of them)
     if (small_round) {
         if (hipError_t e = launch_round_stream(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx,
                                                q_prob, q_count, q_mass, q_lse, tgt_logits, ld_tgt, (int)rows,
-                                               tgt_max, tgt_sum, tgt_lse, s))
+                                               tgt_max, tgt_sum, tgt_lse, workspace, s))
             return hip_status(e);
     } else {
         if (hipError_t e = launch_compress(draft_logits, dtype, ld_draft, n_draft, V, temperature, k, top_p, q_idx, q_prob,
@@ -179,7 +178,7 @@ int picospec_round(const void* draft_logits, const void* tgt_logits, int dtype, 
     }
     return hip_status(launch_decide(tgt_logits, dtype, ld_tgt, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
                                     q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
-                                    verify_flags, out_tok, resid_mass, residual_flags, workspace, rows, s));
+                                    verify_flags, out_tok, resid_mass, residual_flags, workspace, rows, small_round, s));
 }
 
 // ---- verification and draw on records that exist
@@ -208,7 +207,7 @@ int picospec_verify_sample(const void* tgt_logits, int dtype, int64_t ld, int32_
         return hip_status(e);
     return hip_status(launch_decide(tgt_logits, dtype, ld, V, temperature, B, seq_off, draft_tok, q_idx, q_prob,
                                     q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok,
-                                    verify_flags, out_tok, resid_mass, residual_flags, workspace, rows, s));
+                                    verify_flags, out_tok, resid_mass, residual_flags, workspace, rows, false, s));
 }
 
 // ---- wire messages
@@ -386,8 +385,10 @@ size_t picospec_workspace_bytes(int which_call, int dtype, int32_t rows, int32_t
     (void)k;
     if (rows < 0 || V < 1 || V > kMaxV) return 0;
     switch (which_call) {                       // the calls that can keep the target rows' segment table
-        case PICOSPEC_CALL_VERIFY: case PICOSPEC_CALL_SAMPLE_RESIDUAL: case PICOSPEC_CALL_ROUND: case PICOSPEC_CALL_VERIFY_SAMPLE:
+        case PICOSPEC_CALL_VERIFY: case PICOSPEC_CALL_SAMPLE_RESIDUAL: case PICOSPEC_CALL_VERIFY_SAMPLE:
             return seg_table_bytes(dtype, rows, V);
+        case PICOSPEC_CALL_ROUND:               // (a small round lays the table out for its own launch shape)
+            return round_seg_table_bytes(dtype, rows, V);
         default:
             return 0;                           // every other kernel keeps its intermediate state in LDS
     }

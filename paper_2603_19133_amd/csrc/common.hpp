@@ -369,17 +369,24 @@ __device__ __forceinline__ void row_stats_row(
 // with r an integer-valued reference exponent that is the same for the whole wave (every lane adds against it, so the
 // trip's sum is one wave-wide addition; it moves up, and the lanes' running sums are rescaled, only when an element
 // lies more than 2^64 above it: the check is one compare per trip).  Row layout of the table: seg[row * seg_stride + s].
-template <bool BF16, int NV, int THREADS>
+// STAGE_GIVEN: the caller lends kSegStage float2 of LDS for the row's table (a kernel whose workgroups hold a
+// large buffer for another job); otherwise the function owns them.
+constexpr int kSegStage = 1040;                  // segments of the longest row (2^20 elements)
+template <bool BF16, int NV, int THREADS, bool STAGE_GIVEN = false>
 __device__ __forceinline__ void row_stats_seg_row(
     const int64_t row, const void* __restrict__ logits, int64_t ld, int V, float inv_T,
     float* __restrict__ row_max, float* __restrict__ row_sum, float* __restrict__ row_lse,
-    float2* __restrict__ seg, int seg_stride)
+    float2* __restrict__ seg, int seg_stride, float2* stage = nullptr)
 {
     constexpr int WAVES = THREADS / kWave;
     __shared__ double red[2 * WAVES];
     // the row's table is gathered in LDS and written once, in whole lines, at the end of the row
-    constexpr int kSegLds = 1040;                // segments of the longest row (2^20 elements)
-    __shared__ float2 seg_lds[kSegLds];
+    constexpr int kSegLds = kSegStage;
+    float2* seg_lds = stage;
+    if constexpr (!STAGE_GIVEN) {
+        __shared__ float2 own_stage[kSegLds];
+        seg_lds = own_stage;
+    }
     constexpr int N = Vec<BF16>::N, E = NV * N, TILE_VECS = THREADS * NV;
     static_assert(E <= 32, "one bit of the validity mask per element");
     const int tid = threadIdx.x, lane = tid & (kWave - 1);

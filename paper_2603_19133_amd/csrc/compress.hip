@@ -1213,11 +1213,22 @@ __global__ __launch_bounds__(kT, 2) void round_stream_kernel(
     int32_t* __restrict__ idx, float* __restrict__ prob, int32_t* __restrict__ count,
     float* __restrict__ mass, float* __restrict__ lse,
     const void* __restrict__ tgt_logits, int64_t ld_t,
-    float* __restrict__ tgt_max, float* __restrict__ tgt_sum, float* __restrict__ tgt_lse)
+    float* __restrict__ tgt_max, float* __restrict__ tgt_sum, float* __restrict__ tgt_lse,
+    SegHeader* __restrict__ seg_header, int seg_stride)
 {
     if ((int)blockIdx.x < n_draft) {
         compress_row<BF16, false, false>(blockIdx.x, n_draft, draft_logits, ld_d, V, inv_T, k, top_p, idx, prob, count, mass, lse,
                                   nullptr, nullptr, 0);
+    } else if (seg_header) {
+        // with the target rows' segment table (the draw then needs no second pass over its row); the row's table is
+        // staged in the LDS that a compressing workgroup uses for its candidates
+        extern __shared__ __align__(16) unsigned char smem_raw[];
+        static_assert(sizeof(CompressShared<kCapBig>) >= kSegStage * sizeof(float2), "the staged table fits the candidate buffer");
+        if ((int)blockIdx.x == n_draft && threadIdx.x == 0)
+            *seg_header = SegHeader{kSegMagic, kRoundStatsNV<BF16> * kWave, seg_stride, (int32_t)(gridDim.x - n_draft)};
+        row_stats_seg_row<BF16, kRoundStatsNV<BF16>, kT, true>((int64_t)blockIdx.x - n_draft, tgt_logits, ld_t, V, inv_T, tgt_max, tgt_sum,
+                                                                tgt_lse, reinterpret_cast<float2*>(seg_header + 1), seg_stride,
+                                                                reinterpret_cast<float2*>(smem_raw));
     } else {
         row_stats_row<BF16, 2, kT>((int64_t)blockIdx.x - n_draft, tgt_logits, ld_t, V, inv_T, tgt_max, tgt_sum, tgt_lse);
     }
@@ -1405,7 +1416,7 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
 hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d, int n_draft, int V, float temperature,
                                int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
                                const void* tgt_logits, int64_t ld_t, int n_target,
-                               float* tgt_max, float* tgt_sum, float* tgt_lse, hipStream_t stream)
+                               float* tgt_max, float* tgt_sum, float* tgt_lse, void* seg_table, hipStream_t stream)
 {
     static DeviceFlags limit_raised[2] = {};
     const size_t smem = sizeof(CompressShared<kCapBig>);
@@ -1419,8 +1430,11 @@ hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d
     }
     if (n_draft + n_target == 0) return hipSuccess;
     const float inv_T = 1.0f / temperature;
-    if (which) hipLaunchKernelGGL(b16, dim3(n_draft + n_target), dim3(kT), smem, stream, draft_logits, ld_d, n_draft, V, inv_T, k, top_p, idx, prob, count, mass, lse, tgt_logits, ld_t, tgt_max, tgt_sum, tgt_lse);
-    else       hipLaunchKernelGGL(f32, dim3(n_draft + n_target), dim3(kT), smem, stream, draft_logits, ld_d, n_draft, V, inv_T, k, top_p, idx, prob, count, mass, lse, tgt_logits, ld_t, tgt_max, tgt_sum, tgt_lse);
+    if (n_target == 0) seg_table = nullptr;
+    SegHeader* const header = (SegHeader*)seg_table;
+    const int stride = round_stats_shape(dtype, V).stride;
+    if (which) hipLaunchKernelGGL(b16, dim3(n_draft + n_target), dim3(kT), smem, stream, draft_logits, ld_d, n_draft, V, inv_T, k, top_p, idx, prob, count, mass, lse, tgt_logits, ld_t, tgt_max, tgt_sum, tgt_lse, header, stride);
+    else       hipLaunchKernelGGL(f32, dim3(n_draft + n_target), dim3(kT), smem, stream, draft_logits, ld_d, n_draft, V, inv_T, k, top_p, idx, prob, count, mass, lse, tgt_logits, ld_t, tgt_max, tgt_sum, tgt_lse, header, stride);
     return hipGetLastError();
 }
 

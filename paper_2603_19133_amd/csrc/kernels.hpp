@@ -8,6 +8,8 @@
 #include <atomic>
 #include <cmath>
 
+#include "rowspan.hpp"
+
 namespace picospec {
 
 constexpr int kMaxK = 4096;          // candidate buffer in LDS holds 16384 entries; k beyond this is refused
@@ -65,7 +67,7 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
 hipError_t launch_round_stream(const void* draft_logits, int dtype, int64_t ld_d, int n_draft, int V, float temperature,
                                int k, float top_p, int32_t* idx, float* prob, int32_t* count, float* mass, float* lse,
                                const void* tgt_logits, int64_t ld_t, int n_target,
-                               float* tgt_max, float* tgt_sum, float* tgt_lse, hipStream_t stream);
+                               float* tgt_max, float* tgt_sum, float* tgt_lse, void* seg_table, hipStream_t stream);
 
 hipError_t launch_sample_draft(const int32_t* idx, const float* prob, const int32_t* count, const float* mass,
                                int k, int n_rows, const float* uniforms, int32_t* tok, float* q_scalar,
@@ -88,11 +90,31 @@ inline StatsShape stats_shape(int dtype, int64_t n_rows, int V) {
     sh.stride = (int)((nq_max + tile_vecs - 1) / tile_vecs) * (sh.threads / 64);
     return sh;
 }
+// ... and of the target rows of a small round, whose statistics run in 512-thread workgroups next to the compression
+// (launch_round_stream): vectors per lane and trip chosen so that a row of the longest vocabulary has as many
+// segments as above
+template <bool BF16> constexpr int kRoundStatsNV = BF16 ? 2 : 4;
+inline StatsShape round_stats_shape(int dtype, int V) {
+    StatsShape sh;
+    sh.threads = kCompressThreads;
+    sh.nv = dtype == 1 ? kRoundStatsNV<true> : kRoundStatsNV<false>;
+    const int esz = dtype == 1 ? 2 : 4;
+    const int64_t nq_max = ((int64_t)V * esz + 15) / 16 + 1;
+    const int tile_vecs = sh.threads * sh.nv;
+    sh.seg_vecs = 64 * sh.nv;
+    sh.stride = (int)((nq_max + tile_vecs - 1) / tile_vecs) * (sh.threads / 64);
+    return sh;
+}
 // bytes of the segment table of `rows` rows (16-byte header in front: see SegHeader)
 struct SegHeader { int32_t magic, seg_vecs, stride, rows; };
 constexpr int32_t kSegMagic = 0x53454731;
 inline size_t seg_table_bytes(int dtype, int64_t rows, int V) {
     return sizeof(SegHeader) + (size_t)rows * (size_t)stats_shape(dtype, rows, V).stride * 8;
+}
+// ... of a round's target rows, whichever of the two schedules the round takes
+inline size_t round_seg_table_bytes(int dtype, int64_t rows, int V) {
+    const size_t small = sizeof(SegHeader) + (size_t)rows * (size_t)round_stats_shape(dtype, V).stride * 8;
+    return small > seg_table_bytes(dtype, rows, V) ? small : seg_table_bytes(dtype, rows, V);
 }
 
 // seg (nullable): the segment table, seg_stride entries per row
@@ -121,13 +143,15 @@ hipError_t launch_residual(const void* tgt_logits, int dtype, int64_t ld, int V,
                            int32_t* out_tok, float* resid_mass, uint32_t* flags, const void* seg_table, int64_t n_rows, hipStream_t stream);
 
 // acceptance and residual draw of every sequence in one launch; seg_table (nullable, also in launch_residual): the
-// table of the n_rows target rows from launch_row_stats, with which the draw does not stream its row again
+// table of the n_rows target rows from launch_row_stats (small_round_table: from launch_round_stream, whose layout
+// differs), with which the draw does not stream its row again
 hipError_t launch_decide(const void* tgt_logits, int dtype, int64_t ld, int V, float temperature,
                          int B, const int32_t* seq_off, const int32_t* draft_tok,
                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                          int k, int renorm, const float* uniforms, const float* tgt_max, const float* tgt_sum,
                          int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
-                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, const void* seg_table, int64_t n_rows, hipStream_t stream);
+                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, const void* seg_table, int64_t n_rows,
+                         bool small_round_table, hipStream_t stream);
 
 hipError_t launch_resample_sparse(const void* draft_logits, int dtype, int64_t ld, int V, float temperature,
                                   int B, const int32_t* seq_off, const int32_t* n_accept,

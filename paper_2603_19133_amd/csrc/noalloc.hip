@@ -71,7 +71,7 @@ int picospec_verify_sample_static(const void* tgt_logits, int dtype, int64_t ld,
         return PICOSPEC_EHIP;
     return launch_decide(tgt_logits, dtype, ld, V, temperature, B, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass,
                          k, renorm, uniforms, tgt_max, tgt_sum, n_accept, p_tok, q_tok, verify_flags, out_tok, resid_mass,
-                         residual_flags, table, rows, s) == hipSuccess ? PICOSPEC_OK : PICOSPEC_EHIP;
+                         residual_flags, table, rows, false, s) == hipSuccess ? PICOSPEC_OK : PICOSPEC_EHIP;
 }
 
 }  // extern "C"

@@ -121,12 +121,13 @@ hipError_t launch_decide(const void* tgt_logits, int dtype, int64_t ld, int V, f
                          const int32_t* q_idx, const float* q_prob, const int32_t* q_count, const float* q_mass,
                          int k, int renorm, const float* uniforms, const float* tgt_max, const float* tgt_sum,
                          int32_t* n_accept, float* p_tok, float* q_tok, uint32_t* flags,
-                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, const void* seg_table, int64_t n_rows, hipStream_t stream)
+                         int32_t* out_tok, float* resid_mass, uint32_t* res_flags, const void* seg_table, int64_t n_rows,
+                         bool small_round_table, hipStream_t stream)
 {
     if (seg_table) {
         if (B == 0) return hipSuccess;
         const float it = 1.0f / temperature;
-        const StatsShape sh = stats_shape(dtype, n_rows, V);
+        const StatsShape sh = small_round_table ? round_stats_shape(dtype, V) : stats_shape(dtype, n_rows, V);
         if (dtype == 1) hipLaunchKernelGGL(decide_seg_kernel<true>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, it, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, (const SegHeader*)seg_table, sh.seg_vecs, sh.stride, n_accept, p_tok, q_tok, flags, out_tok, resid_mass, res_flags);
         else            hipLaunchKernelGGL(decide_seg_kernel<false>, dim3(B), dim3(kThreads), 0, stream, tgt_logits, ld, V, it, seq_off, draft_tok, q_idx, q_prob, q_count, q_mass, k, renorm, uniforms, tgt_max, tgt_sum, (const SegHeader*)seg_table, sh.seg_vecs, sh.stride, n_accept, p_tok, q_tok, flags, out_tok, resid_mass, res_flags);
         return hipGetLastError();
