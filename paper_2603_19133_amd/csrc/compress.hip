@@ -1369,14 +1369,14 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
     // the latter with the large or the small candidate buffer
     const void* const kernels[8] = {(const void*)compress_kernel<false, false, false>, (const void*)compress_kernel<true, false, false>,
                                     (const void*)compress_kernel<false, false, true>, (const void*)compress_kernel<true, false, true>,
-                                    (const void*)compress_kernel<false, true, true>, (const void*)compress_kernel<true, true, true>,
+                                    nullptr /* (the small buffer serves bf16 rows only) */, (const void*)compress_kernel<true, true, true>,
                                     (const void*)compress_retry_kernel<false>, (const void*)compress_retry_kernel<true>};
     const size_t smem_big = sizeof(CompressShared<kCapBig>), smem_small = sizeof(CompressShared<kCapSmall>);
     int dev = 0;
     {   // (every variant of the dtype: which of them a call takes depends on its sizes)
         hipError_t e = hipSuccess;
         for (int v = 0; v < 4 && e == hipSuccess; ++v)
-            e = raise_lds_limit_once(kernels[2 * v + bf], v == 2 ? smem_small : smem_big, limit_raised[2 * v + bf], dev);
+            if (kernels[2 * v + bf]) e = raise_lds_limit_once(kernels[2 * v + bf], v == 2 ? smem_small : smem_big, limit_raised[2 * v + bf], dev);
         if (e != hipSuccess) return e;
     }
     if (n_rows == 0) return hipSuccess;
@@ -1388,7 +1388,9 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
     // Calls of more rows than the chip holds at a time take the fast kernels (fewer registers: the careful pass is
     // not in them) and pay one small launch more; smaller calls are bound by that launch and take the general kernel.
     const bool fast = cus > 0 && n_rows > 2 * cus && V > kCompressSample;
-    const bool small = fast && small_variant_serves(k, V);
+    // (fp32 rows stream faster from two workgroups per CU with the large buffer than from three with the small one,
+    //  measured at every record length; bf16 rows, which cost twice the arithmetic per byte, gain from the third)
+    const bool small = fast && bf && small_variant_serves(k, V);
     // rows resident at a time (2 workgroups per CU, 3 of the small variant): the distance of the look-ahead loads
     // (no look-ahead with a row map: the next row is not known from the row number)
     const int ahead = (!seq_off && cus > 0) ? (small ? 3 : 2) * cus : 0;
@@ -1398,7 +1400,7 @@ hipError_t launch_compress(const void* logits, int dtype, int64_t ld, int n_rows
 #define PICOSPEC_RETRY(BF) \
     hipLaunchKernelGGL((compress_retry_kernel<BF>), dim3(min(64, (n_rows + kT - 1) / kT)), dim3(kT), smem_big, stream, logits, ld, n_rows, V, inv_T, k, top_p, idx, prob, count, mass, lse, seq_off, n_accept)
     if (small) {
-        if (bf) PICOSPEC_COMPRESS(true, true, true, smem_small); else PICOSPEC_COMPRESS(false, true, true, smem_small);
+        PICOSPEC_COMPRESS(true, true, true, smem_small);
     } else if (fast) {
         if (bf) PICOSPEC_COMPRESS(true, false, true, smem_big); else PICOSPEC_COMPRESS(false, false, true, smem_big);
     } else {
