@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic of one compress launch (bytes), a constant taken from the rocprofv3 --pmc runs summarised under
 # profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters' reading for a plain copy of known size): it is
 # NOT measured in this run, and the JSON line says so next to it.
-PROFILED_TRAFFIC = {"cfg4": (2.672e9, "profiles/cfg4_round_kernels.md"), "cfg5": (1.387e9, "profiles/cfg5_cfg3_round_kernels.md"),
+PROFILED_TRAFFIC = {"cfg4": (2.671e9, "profiles/cfg4_round_kernels.md"), "cfg5": (1.403e9, "profiles/cfg5_cfg3_round_kernels.md"),
                     "cfg3": (1.364e8, "profiles/cfg5_cfg3_round_kernels.md")}
 # distinct resident input sets a run cycles through, so that no step finds its logits in the caches (cfg4's single set
 # is 22 times the 256 MB Infinity Cache); cfg5's sets are rounds 0..7 of the workload, each with its own draft lengths
@@ -60,6 +60,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=0, help="timed rounds (default 200; cfg5: its 100 consecutive rounds)")
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed steps first: the first twenty or so rounds after start-up run 5-10 %% slower")
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="before the warm-up steps: untimed rounds for this many milliseconds, so that the device has left the dip "
+                         "of its effective shader clock that follows every pause (3-40 ms after work resumes; --burst shows it) "
+                         "whatever --warmup is; 0 switches it off")
     ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences (debugging)")
     ap.add_argument("--sets", type=int, default=0, help="distinct resident input sets to cycle through (default per config)")
@@ -177,6 +181,16 @@ def main() -> int:
         del src, dst
 
     clock_ticks = torch.zeros((2, 2), dtype=torch.int64, device=dev)
+    # Settling (untimed, reported in the JSON line): the device was idle while the inputs were made, and for some tens of
+    # milliseconds after work resumes its effective shader clock dips, which the compress kernel follows.  The rounds
+    # here keep it busy through that; the warm-up steps follow without a pause.
+    settled_rounds = 0
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(4):
+            step(settled_rounds)
+            settled_rounds += 1
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     ps.probe_clock(clock_ticks[0])           # the shader clock at the start of the timed region ...
@@ -250,7 +264,9 @@ def main() -> int:
                                f"k={w.k} top_p={w.top_p}", "draft_rows": N if n_sets == 1 else [x.N for x in sets],
                    "target_rows": N + B if n_sets == 1 else [x.N + x.B for x in sets],
                    "input_sets": n_sets, "segment_table": not args.no_workspace, "protocol": f"{steps} consecutive rounds over {n_sets} resident input set(s), "
-                   "uniforms of its own for every round", "parallelism": "1 GPU"},
+                   "uniforms of its own for every round" + (f"; {settled_rounds} untimed rounds ({args.settle_ms:g} ms) in front of the "
+                   "warm-up steps carry the device through the clock dip that follows a pause" if settled_rounds else ""),
+                   "settle_ms": args.settle_ms, "settle_rounds": settled_rounds, "parallelism": "1 GPU"},
         "round_algorithmic_GBps": alg_total / wall / 1e9,
         "round_frac_of_hbm_peak": None if cache_resident else alg_total / wall / 1e9 / HBM_PEAK_GBS,
         "cache_resident": bool(cache_resident),

@@ -1,8 +1,10 @@
 """CPU oracle for the PicoSpec separate-rejection-sampling path.
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()`` and the
-``cpu_baseline`` leg of ``bench.py``.  Nothing in the product package imports this, and this
-package imports nothing from the product package.
+``cpu_baseline`` leg of ``bench.py``.  Nothing in the product package imports this, and this module
+(the oracle proper) imports nothing from the product package.  ``oracle/downlink_bias.py``, a script that tabulates
+the truncation bias of a K-entry record on synthetic rounds with the oracle alone, takes its inputs from the seeded
+input generators (``paper_2603_19133_amd/workloads.py``, which hold none of the method's arithmetic).
 
 The arithmetic lives in ``picospec_oracle.c`` (plain C, fp64) and the wire formats in
 ``picospec_wire_oracle.c``; this module only builds them with gcc and marshals numpy arrays into them.
