@@ -51,6 +51,7 @@ constexpr int kCapSmall = 5120;             // ... and the variant for records o
 constexpr int kBinsLog2 = 11;
 constexpr int kBins = 1 << kBinsLog2;       // histogram bins of the radix selects / rank sort
 constexpr int kBinsPer = kBins / kT;
+constexpr int kFine = 2 * kBins;            // fine bins of the rank sort: 16-bit counters, two to a histogram word
 constexpr int kIdBits = 20;                 // ids < 2^20 (kMaxV)
 constexpr unsigned kIdMask = (1u << kIdBits) - 1u;
 constexpr int kSortMaxBin = 128;            // beyond this bin size the ordering falls back to a sorting network
@@ -58,7 +59,7 @@ constexpr int kCoarseLog2 = 8;
 constexpr int kCoarse = 1 << kCoarseLog2;   // coarse ranges that steer the fine bins of the rank sort
 
 static_assert(kMaxK <= kCapBig && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
-static_assert(kBins <= 32768, "bin and arrival order of a candidate share one register");
+static_assert(kFine <= 32768, "bin and arrival order of a candidate share one register");
 static_assert(kMaxV <= (1 << kIdBits), "id field of the composite key");
 
 template <int CAP>
@@ -267,7 +268,7 @@ __device__ __forceinline__ void order_prepare(SH& sh, int n) {
     asm volatile("" : "+v"(t));                  // (the address is formed here, not held in a register from the top of the kernel)
     for (int i = t; i < kCoarse; i += kT) sh.coarse[i] = 0;
     zero_hist(sh);
-    if (threadIdx.x == 0) { sh.maxbin = 0; sh.piv_bin = kBins - 1; sh.piv_before = n; }
+    if (threadIdx.x == 0) { sh.maxbin = 0; sh.piv_bin = kFine - 1; sh.piv_before = n; }
 }
 
 // Cut the n <= kCap candidates in the buffer to the min(n, k) largest by composite and order them,
@@ -279,8 +280,8 @@ __device__ __forceinline__ void order_prepare(SH& sh, int n) {
 //     ib is as many id bits as fit next to the key range (all of them for rows with few distinct
 //     logits, so that equal logits spread over the bins by id).
 //   * A coarse histogram of p (kCoarse equal ranges) measures where the candidates lie; each
-//     coarse range then gets a share of the kBins fine bins in proportion to its count, so that
-//     fine bins hold a few candidates each whatever the distribution of the logits.
+//     coarse range then gets a share of the kFine fine bins in proportion to its count, so that
+//     fine bins hold one or two candidates each whatever the distribution of the logits.
 //   * A prefix sum over the fine bins finds the bin in which the k-th largest falls; the
 //     candidates of the bins up to that one are gathered bin by bin, each one's position inside
 //     its bin is the number of larger bin-mates, and the positions below k are kept.
@@ -296,7 +297,8 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
     const int ib = min(32 - kb, vb);                             // id bits that take part
     const int id_drop = vb - ib;
     const int cshift = max(0, kb + ib - kCoarseLog2);            // p >> cshift < kCoarse
-    static_assert(kCoarse <= kT && kCoarse % kWave == 0 && kCoarse <= kBins / 4, "coarse histogram geometry");
+    static_assert(kCoarse <= kT && kCoarse % kWave == 0 && kCoarse <= kFine / 4 && kFine < 65536, "coarse histogram geometry; (fine bins, first fine bin) share a word");
+    static_assert(kCap < 65536, "positions and bin counts are kept in 16 bits");
     // (order_prepare and a barrier behind it have cleared the histograms)
     uint64_t c[kCandPer];
     uint32_t place[kCandPer];
@@ -316,7 +318,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
     // wave builds the table, kCoarse / 64 consecutive ranges per lane
     if (wave == 0) {
         constexpr int kPerLane = kCoarse / kWave;
-        constexpr int kShared = kBins - kCoarse - kCoarse / 2;      // leaves room for the "at least one" and for rounding
+        constexpr int kShared = kFine - kCoarse - kCoarse / 2;      // leaves room for the "at least one" and for rounding
         const float share = (float)kShared / (float)n;
         unsigned nf[kPerLane], loc = 0;
 #pragma unroll
@@ -339,14 +341,23 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
             const unsigned t = sh.coarse[min(place[j] >> cshift, (uint32_t)(kCoarse - 1))];
             const uint32_t frac = cshift ? (place[j] << (32 - cshift)) : 0u;   // position inside the coarse range, as a 0.32 fraction
             const int bin = (int)(t & 0xFFFFu) + (int)__umulhi(frac, t >> 16);
-            meta[j] = (bin << 16) | (int)atomicAdd(&sh.hist[bin], 1u);
+            // (bin 2w in the low half of word w, bin 2w+1 in the high half: a bin holds fewer than 2^16 candidates, so
+            //  the low half never carries into the high one)
+            const int half = (bin & 1) * 16;
+            meta[j] = (bin << 16) | (int)((atomicAdd(&sh.hist[bin >> 1], 1u << half) >> half) & 0xFFFFu);
         }
     }
     __syncthreads();
-    // exclusive prefix over the bins, in place; the bin that holds the k-th largest; the most crowded bin in front of it
-    int h[kBinsPer], loc = 0;
+    // exclusive prefix over the bins, in place (16 bits each: at most kCap candidates); the bin that holds the k-th
+    // largest; the most crowded bin in front of it
+    constexpr int kFinePer = kFine / kT;
+    int h[kFinePer], loc = 0;
 #pragma unroll
-    for (int j = 0; j < kBinsPer; ++j) { h[j] = (int)sh.hist[tid * kBinsPer + j]; loc += h[j]; }
+    for (int j = 0; j < kBinsPer; ++j) {
+        const unsigned w = sh.hist[tid * kBinsPer + j];
+        h[2 * j] = (int)(w & 0xFFFFu); h[2 * j + 1] = (int)(w >> 16);
+        loc += h[2 * j] + h[2 * j + 1];
+    }
     const int incl = wave_scan_incl(loc);
     if (lane == kWave - 1) sh.wtot[wave] = incl;
     __syncthreads();   // every thread has read its counters
@@ -354,14 +365,21 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
 #pragma unroll
     for (int w = 0; w < kW; ++w) excl += (w < wave) ? sh.wtot[w] : 0;
     int big = 0;
+    const uint16_t* const start_of = reinterpret_cast<const uint16_t*>(sh.hist);    // first position of a fine bin, below
 #pragma unroll
     for (int j = 0; j < kBinsPer; ++j) {
-        sh.hist[tid * kBinsPer + j] = (unsigned)excl;
-        if (excl < k) {
-            big = max(big, h[j]);
-            if (excl + h[j] >= k) { sh.piv_bin = tid * kBinsPer + j; sh.piv_before = excl + h[j]; }
+        unsigned w = 0;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int b = 2 * j + u;
+            w |= (unsigned)excl << (16 * u);
+            if (excl < k) {
+                big = max(big, h[b]);
+                if (excl + h[b] >= k) { sh.piv_bin = tid * kFinePer + b; sh.piv_before = excl + h[b]; }
+            }
+            excl += h[b];
         }
-        excl += h[j];
+        sh.hist[tid * kBinsPer + j] = w;
     }
     if (big > kSortMaxBin) atomicMax(&sh.maxbin, big);
     __syncthreads();
@@ -386,7 +404,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
     // gather bin by bin (every candidate is in registers: the buffer may be overwritten)
 #pragma unroll
     for (int j = 0; j < kCandPer; ++j)
-        if (meta[j] >= 0 && (meta[j] >> 16) <= piv) buf[(int)sh.hist[meta[j] >> 16] + (meta[j] & 0xFFFF)] = c[j];
+        if (meta[j] >= 0 && (meta[j] >> 16) <= piv) buf[(int)start_of[meta[j] >> 16] + (meta[j] & 0xFFFF)] = c[j];
     __syncthreads();
     int pos[kCandPer];
 #pragma unroll
@@ -394,8 +412,8 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
         pos[j] = k;
         if (meta[j] >= 0 && (meta[j] >> 16) <= piv) {
             const int bin = meta[j] >> 16;
-            const int s = (int)sh.hist[bin];
-            const int e = bin < piv ? (int)sh.hist[bin + 1] : n_keep;
+            const int s = (int)start_of[bin];
+            const int e = bin < piv ? (int)start_of[bin + 1] : n_keep;
             int larger = 0;
             for (int q = s; q < e; q += 4) {         // four bin-mates per round trip to LDS
                 uint64_t m[4];

@@ -57,6 +57,63 @@ def _case(seed):
     return dict(V=V, k=k, dtype=dtype, T=T, top_p=top_p, shift=shift, pattern=pattern), z.astype(np.float32)
 
 
+def _pattern_rows(rng, pattern, rows, ld, shift):
+    """`rows` rows of one value pattern (the patterns of _case)."""
+    ids = np.arange(ld, dtype=np.float64)
+    z = rng.standard_normal((rows, ld)) * float(rng.choice([0.5, 3.0, 8.0]))
+    if pattern == "zipf":
+        z = -1.2 * np.log(np.stack([rng.permutation(ld) for _ in range(rows)]) + 1.0) + 0.5 * rng.standard_normal((rows, ld))
+    elif pattern == "trend":
+        z = z + float(rng.choice([-12.0, -3.0, 3.0, 12.0])) * ids / ld
+    elif pattern == "head":
+        z = z + np.where(ids < float(rng.choice([300, 4096, 8192, 20000])), float(rng.choice([-8.0, 5.0, 9.0])), 0.0)
+    elif pattern == "masked":
+        keep = rng.random((rows, ld)) < float(rng.choice([0.5, 0.05, 0.005]))
+        keep[:, int(rng.integers(shift, ld))] = True
+        z = np.where(keep, z, -np.inf)
+    elif pattern == "ties":
+        z = np.round(z)
+    elif pattern == "few_values":
+        z = np.round(rng.standard_normal((rows, ld)) * float(rng.choice([0.3, 0.5, 0.7, 1.0])))
+    elif pattern == "spike":                    # one value far above the rest, where the threshold's sample mostly misses it
+        z[np.arange(rows), rng.integers(shift, ld, rows)] = float(rng.choice([90.0, 200.0, 3000.0]))
+    return z
+
+
+N_FULL = int(os.environ.get("PICOSPEC_SWEEP_FULL", "8"))              # calls of more rows than the chip holds at a time
+
+
+@pytest.mark.parametrize("seed", range(N_FULL))
+def test_compress_random_sweep_with_the_chip_full(gpu, seed):
+    """Calls of 530-700 rows (more than two workgroups per CU: the kernels that hold the optimistic pass only, with the large
+    and with the small candidate buffer, and the launch behind them that takes the rows they give up), the value pattern
+    changing every few dozen rows, odd leading dimensions and record lengths across the range."""
+    import parity_util as pu
+    from paper_2603_19133_amd import binding as ps
+    rng = np.random.default_rng(90_000 + SEED0 + seed)
+    V = int(rng.choice([int(rng.integers(8300, 12400)), int(rng.integers(12000, 33000)), int(rng.integers(33000, 70000)),
+                        int(rng.integers(33000, 70000)), int(rng.integers(100_000, 160_000))]))
+    k = int(min(V, 4096, max(1, round(float(np.exp(rng.uniform(np.log(8), np.log(4096))))))))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    T = float(rng.choice([0.5, 1.0, 1.0, 2.0]))
+    shift = int(rng.choice([0, 0, 1, 3]))
+    rows, ld = int(rng.integers(530, 700)), V + shift
+    parts, left = [], rows
+    while left > 0:
+        n = min(left, int(rng.integers(20, 80)))
+        pattern = str(rng.choice(["normal", "normal", "zipf", "trend", "head", "masked", "ties", "few_values", "spike"]))
+        parts.append(_pattern_rows(rng, pattern, n, ld, shift).astype(np.float32))
+        left -= n
+    z = np.concatenate(parts)
+    print("[case] sweep chip full", seed, dict(V=V, k=k, dtype=dtype, T=T, shift=shift, rows=rows), flush=True)
+    stored = z if dtype == "f32" else W.to_bf16_bits(z)
+    dev = pu.to_device(stored, gpu)
+    o = oracle.compress(np.ascontiguousarray(stored[:, shift:]), V, T, k, 0.0)
+    g = ps.compress(dev[:, shift:], V, T, k, 0.0)
+    torch.cuda.synchronize()
+    pu.compare_compress(g, o, 0.0)
+
+
 @pytest.mark.parametrize("block", range(8))
 def test_compress_random_sweep(gpu, block):
     import parity_util as pu
