@@ -55,7 +55,7 @@ constexpr int kFine = 2 * kBins;            // fine bins of the rank sort: 16-bi
 constexpr int kIdBits = 20;                 // ids < 2^20 (kMaxV)
 constexpr unsigned kIdMask = (1u << kIdBits) - 1u;
 constexpr int kSortMaxBin = 128;            // beyond this bin size the ordering falls back to a sorting network
-constexpr int kCoarseLog2 = 8;
+constexpr int kCoarseLog2 = 9;
 constexpr int kCoarse = 1 << kCoarseLog2;   // coarse ranges that steer the fine bins of the rank sort
 
 static_assert(kMaxK <= kCapBig && (kMaxK & (kMaxK - 1)) == 0, "the sorting network pads to a power of two inside the buffer");
