@@ -1,10 +1,14 @@
 // Sparse Top-K compression of vocabulary distributions (paper Section 3.3, Eq. 4) fused with the
-// softmax statistics: one workgroup of 512 threads per row, two workgroups per CU, one HBM pass
-// per row.
+// softmax statistics: one workgroup of 512 threads per row, two workgroups per CU (three with the
+// small candidate buffer), one HBM pass per row.  Three kernels per dtype share the code below
+// (launch_compress chooses): the general one (optimistic pass, then the safe pass for the rows that
+// lose it), the fast ones that hold the optimistic pass only, with the large or the small candidate
+// buffer, and mark the rows they give up, and the retry kernel that runs the general code on those.
 //
 // Streaming selection.  A row is read with buffer loads (descriptor base + scalar offset + one
 // constant per-lane offset) in sub-tiles of two 16-byte vectors per thread through a ring of four
-// register buffers (three sub-tiles in flight behind the one being processed).
+// register buffers (three sub-tiles in flight behind the one being processed; one vector and a ring
+// of five in the bf16 kernel with the small buffer).
 //   * A sample of 8192 elements stays in registers while a histogram over their values (one pass on a
 //     linear scale, else two radix passes over the order-preserving keys) finds a threshold: a value
 //     with at least r of the sample's elements at or above it.
@@ -13,7 +17,8 @@
 //     chosen (optimistic_rank, kernels.hpp) so that the row is expected to hold k plus a safety margin at or above the
 //     threshold.  The row is then streamed from its start: every element at or above the threshold
 //     claims a slot of the candidate buffer in LDS with an atomic of its own and writes (value, id)
-//     there; the softmax arithmetic sits between claim and write.  If the row ends with at least k
+//     there; the softmax arithmetic sits between claim and write, and runs against a reference exponent
+//     fixed from the sample (no running maximum: the row's maximum is its largest candidate).  If the row ends with at least k
 //     candidates that fit the buffer, the exact top k is among them, because nothing at or above the
 //     threshold was dropped.  Waves run free in this pass; too many or too few candidates give the
 //     pass up.
