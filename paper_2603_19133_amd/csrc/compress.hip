@@ -301,7 +301,15 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
     const int vb = V > 1 ? 32 - __clz(V - 1) : 0;                // bits of an id
     const int ib = min(32 - kb, vb);                             // id bits that take part
     const int id_drop = vb - ib;
-    const int cshift = max(0, kb + ib - kCoarseLog2);            // p >> cshift < kCoarse
+    // The coarse ranges tile the places that occur, [0, (kr + 1) << ib), exactly: range = floor(p * kCoarse / that),
+    // as the high word of p times a 0.32 fixed-point factor; the low word is the position inside the range.  (Ranges
+    // that tile the next power of two leave up to half of them, and of the fine bins of the range that holds the
+    // threshold - the most crowded one - to places that do not occur.)  Few places: one range per place.
+    const uint64_t n_places = ((uint64_t)kr + 1u) << ib;           // <= 2^32
+    const bool one_each = n_places <= (uint64_t)kCoarse;
+    const uint32_t to_range = one_each ? 0u : (uint32_t)(((uint64_t)kCoarse << 32) / n_places);   // < 2^32 as n_places > kCoarse
+    auto range_of = [&](uint32_t p) { return one_each ? min(p, (uint32_t)(kCoarse - 1)) : min(__umulhi(p, to_range), (uint32_t)(kCoarse - 1)); };
+    auto within_range = [&](uint32_t p) { return one_each ? 0u : p * to_range; };   // position inside the range, as a 0.32 fraction
     static_assert(kCoarse <= kT && kCoarse % kWave == 0 && kCoarse <= kFine / 4 && kFine < 65536, "coarse histogram geometry; (fine bins, first fine bin) share a word");
     static_assert(kCap < 65536, "positions and bin counts are kept in 16 bits");
     // (order_prepare and a barrier behind it have cleared the histograms)
@@ -315,7 +323,7 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
             const uint32_t bits = sh.cand_val[i], id = sh.cand_id[i];
             c[j] = composite<BF16>(bits, id);
             place[j] = ib < 32 ? ((key_hi - short_key<BF16>(bits)) << ib) | (id >> id_drop) : (id >> id_drop);
-            atomicAdd(&sh.coarse[min(place[j] >> cshift, (uint32_t)(kCoarse - 1))], 1u);
+            atomicAdd(&sh.coarse[range_of(place[j])], 1u);
         }
     }
     __syncthreads();
@@ -343,8 +351,8 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
         const int i = tid + j * kT;
         meta[j] = -1;
         if (i < n) {
-            const unsigned t = sh.coarse[min(place[j] >> cshift, (uint32_t)(kCoarse - 1))];
-            const uint32_t frac = cshift ? (place[j] << (32 - cshift)) : 0u;   // position inside the coarse range, as a 0.32 fraction
+            const unsigned t = sh.coarse[range_of(place[j])];
+            const uint32_t frac = within_range(place[j]);
             const int bin = (int)(t & 0xFFFFu) + (int)__umulhi(frac, t >> 16);
             // (bin 2w in the low half of word w, bin 2w+1 in the high half: a bin holds fewer than 2^16 candidates, so
             //  the low half never carries into the high one)
