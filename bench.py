@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic of one compress launch (bytes), a constant taken from the rocprofv3 --pmc runs summarised under
 # profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the same counters' reading for a plain copy of known size): it is
 # NOT measured in this run, and the JSON line says so next to it.
-PROFILED_TRAFFIC = {"cfg4": (2.671e9, "profiles/cfg4_round_kernels.md"), "cfg5": (1.403e9, "profiles/cfg5_cfg3_round_kernels.md"),
+PROFILED_TRAFFIC = {"cfg4": (2.672e9, "profiles/cfg4_round_kernels.md"), "cfg5": (1.401e9, "profiles/cfg5_cfg3_round_kernels.md"),
                     "cfg3": (1.364e8, "profiles/cfg5_cfg3_round_kernels.md")}
 # distinct resident input sets a run cycles through, so that no step finds its logits in the caches (cfg4's single set
 # is 22 times the 256 MB Infinity Cache); cfg5's sets are rounds 0..7 of the workload, each with its own draft lengths
