@@ -447,10 +447,10 @@ __device__ __forceinline__ const uint64_t* order_top_k(SH& sh, int n, int k, int
 
 // One row of the compression: the workgroup that runs this writes record `row` of `n_rows`.
 // SMALL: records of up to kMaxK / 2 entries on rows whose expected candidates fit the smaller buffer (the host
-// decides: launch_compress) - 42 KB of LDS and 80 registers, so that three workgroups share a CU.  This variant
-// holds the optimistic pass only (what the careful pass keeps alive across it costs the registers that the third
-// workgroup needs): a row whose pass fails, or to which it does not apply, gets count = kRetryRow and nothing
-// else, and a second launch of the general kernel, which skips every other row, takes it.
+// decides: launch_compress) - 51 KB of LDS and at most 80 registers, so that three workgroups share a CU.
+// FAST: the optimistic pass only (what the careful pass keeps alive across it costs registers, those that the third
+// workgroup needs among them): a row whose pass fails, or to which it does not apply, gets count = kRetryRow and
+// nothing else, and a second, small launch that runs the general code on the marked rows takes it.
 template <bool BF16, bool SMALL, bool FAST = SMALL>
 __device__ __forceinline__ void compress_row(
     const int64_t row, const int n_rows,
